@@ -1,0 +1,130 @@
+/*
+ * tfla_mlstm.h -- C ABI of the MI355X (gfx950) chunkwise-parallel mLSTM kernels with
+ * Tiled Flash Linear Attention.
+ *
+ * The library computes the hidden states h~_t of the mLSTM cell (paper Sec. 2.1; the NORM
+ * layer and the output gate are not part of the kernel, as in Sec. 2.2) in the
+ * chunkwise-parallel formulation (Sec. 2.2, App. B.2) with two levels of sequence
+ * parallelism (Sec. 3, App. C), for the exponential-input-gate mLSTM ("mLSTMexp") and for the
+ * sigmoid-input-gate variant mLSTMsig (Sec. 4.1), and the matching backward pass (App. B.3,
+ * App. C.4).  The result does not depend on the chunk size.
+ *
+ * Conventions (all entry points)
+ *  - Every tensor pointer is a DEVICE pointer to a dense row-major array owned by the
+ *    caller.  The library never allocates, frees or synchronises; all work is enqueued on
+ *    `stream` (a hipStream_t passed as void*; NULL = the default stream).  Outputs are
+ *    overwritten, never accumulated into.
+ *  - q, k: (B, NH, T, dqk); v, H, dH: (B, NH, T, dhv); element type given by `dtype`
+ *    (TFLA_F32: float, TFLA_BF16: bfloat16).  Gate pre-activations i_pre, f_pre and all
+ *    per-step scalars: (B, NH, T) float.  States: C (B, NH, dqk, dhv) float,
+ *    n (B, NH, dqk) float, m (B, NH) float.
+ *  - q is passed unscaled; the kernels apply 1/sqrt(dqk) (it is part of the h~_t equation
+ *    of Sec. 2.1).
+ *  - States are in the stabilised coordinates of the recurrence (true C = C * exp(m)),
+ *    exactly as the recurrence of Sec. 2.1 produces them, so a returned (Cn, nn, mn) can be
+ *    passed as (C0, n0, m0) of the next call (chunked continuation of a long sequence).
+ *  - variant TFLA_SIG has no normaliser and no max state: n0, m0 and eps are ignored and
+ *    nn, mn, n_out, m_out are filled with zeros when non-NULL.
+ *  - eps is added to the denominator max{|n^T q~|, exp(-m)}; eps = 0 is the paper's formula.
+ *  - Restrictions: T % chunk == 0, chunk % 64 == 0, 64 <= chunk <= 2048,
+ *    T / chunk <= 4096, dqk and dhv multiples of 64 and <= 512 (<= 256 for TFLA_F32).
+ *  - Return value: TFLA_OK (0) on success; a negative TFLA_ERR_* code for an invalid
+ *    argument (checked before anything is launched, nothing is written); a positive value is
+ *    the hipError_t of a failed launch.  No entry point throws or aborts.
+ */
+#ifndef TFLA_MLSTM_H
+#define TFLA_MLSTM_H
+
+#include <stddef.h>
+
+#if defined(__GNUC__)
+#define TFLA_API __attribute__((visibility("default")))
+#else
+#define TFLA_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { TFLA_EXP = 0, TFLA_SIG = 1 };           /* variant: exponential / sigmoid input gate */
+enum { TFLA_F32 = 0, TFLA_BF16 = 1 };          /* dtype of q, k, v, H, dH, dq, dk, dv        */
+enum { TFLA_FWD = 0, TFLA_BWD = 1 };           /* direction for tfla_mlstm_workspace_bytes   */
+
+enum {
+    TFLA_OK = 0,
+    TFLA_ERR_NULL = -1,        /* a required pointer is NULL                                 */
+    TFLA_ERR_SHAPE = -2,       /* a dimension is non-positive or violates the restrictions   */
+    TFLA_ERR_CHUNK = -3,       /* chunk does not divide T or is not an allowed chunk size    */
+    TFLA_ERR_ENUM = -4,        /* unknown variant / dtype / direction                        */
+    TFLA_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned (256 B) or too small            */
+    TFLA_ERR_STATE = -6        /* C0/n0/m0 (or Cn/nn/mn) only partly given                   */
+};
+
+/*
+ * Forward pass (Sec. 2.2 / App. B.2 for the mathematics, Sec. 3 / App. C for the tiling).
+ *   in : q, k, v, i_pre, f_pre; optional initial state C0, n0, m0 (all three NULL = zero
+ *        state with m0 = 0; for TFLA_SIG only C0 is read and n0/m0 may be NULL)
+ *   out: H (required); optional final state Cn, nn, mn (each may be NULL);
+ *        optional n_out, m_out (B, NH, T): the signed normaliser n_t^T q~_t and the max state
+ *        m_t of every step, which tfla_mlstm_bwd needs for TFLA_EXP.
+ *   workspace: device scratch of at least tfla_mlstm_workspace_bytes(TFLA_FWD, ...) bytes,
+ *        256-byte aligned; its contents are undefined afterwards.
+ */
+TFLA_API int tfla_mlstm_fwd(const void* q, const void* k, const void* v,
+                   const float* i_pre, const float* f_pre,
+                   const float* C0, const float* n0, const float* m0,
+                   int B, int NH, int T, int dqk, int dhv,
+                   int chunk, int variant, int dtype, float eps,
+                   void* H, float* Cn, float* nn, float* mn,
+                   float* n_out, float* m_out,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward pass (App. B.3, App. C.4).  Computes the gradient of
+ *     sum_t <dH_t, H_t>  +  <dCn, C_T>
+ * with respect to q, k, v, i_pre, f_pre and C0, where -- as the paper prescribes (App. B.3,
+ * "Gradients Through Normalizer States") -- the normaliser h_denom and the max states are
+ * treated as constants.  For TFLA_SIG this is the exact gradient.
+ *   in : q, k, v, i_pre, f_pre, C0/n0/m0 as in the forward call; n_out, m_out as written by
+ *        the forward call (required for TFLA_EXP, ignored for TFLA_SIG); dH (required);
+ *        dCn (B, NH, dqk, dhv) gradient w.r.t. the returned final state, or NULL for zero.
+ *   out: dq, dk (B, NH, T, dqk), dv (B, NH, T, dhv) in `dtype`; d_i_pre, d_f_pre (B, NH, T)
+ *        float; dC0 (B, NH, dqk, dhv) float or NULL.  No gradient is produced for n0, m0.
+ *   workspace: at least tfla_mlstm_workspace_bytes(TFLA_BWD, ...) bytes, 256-byte aligned.
+ *        The chunk states are recomputed inside this call; nothing but n_out/m_out has to be
+ *        kept from the forward call.
+ */
+TFLA_API int tfla_mlstm_bwd(const void* q, const void* k, const void* v,
+                   const float* i_pre, const float* f_pre,
+                   const float* C0, const float* n0, const float* m0,
+                   const float* n_out, const float* m_out,
+                   const void* dH, const float* dCn,
+                   int B, int NH, int T, int dqk, int dhv,
+                   int chunk, int variant, int dtype, float eps,
+                   void* dq, void* dk, void* dv,
+                   float* d_i_pre, float* d_f_pre, float* dC0,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Bytes of workspace the call with these arguments needs (host function, launches nothing).
+ * Returns 0 if the arguments are invalid.
+ */
+TFLA_API size_t tfla_mlstm_workspace_bytes(int direction, int B, int NH, int T, int dqk, int dhv,
+                                  int chunk, int variant, int dtype);
+
+/* Validates the arguments of a forward / backward call without launching anything; returns
+ * the status the call would return before its first launch (host function). */
+TFLA_API int tfla_mlstm_check(int direction, int B, int NH, int T, int dqk, int dhv,
+                     int chunk, int variant, int dtype);
+
+/* Human-readable text for a status code (static storage). */
+TFLA_API const char* tfla_status_string(int status);
+
+/* Library version, major * 1000 + minor. */
+TFLA_API int tfla_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TFLA_MLSTM_H */

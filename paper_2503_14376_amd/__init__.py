@@ -1,0 +1,12 @@
+"""MI355X-native chunkwise-parallel mLSTM kernels (Tiled Flash Linear Attention).
+
+Thin binding over the C ABI of lib/libtfla_mlstm.so (see include/tfla_mlstm.h): argument
+marshalling only, every step of the computation runs in the HIP kernels.  PyTorch is used
+for device memory and streams.  There is no CPU or eager fallback: if the library has not
+been built (python -m paper_2503_14376_amd.build) importing the binding fails loudly.
+"""
+from .binding import (BF16, EXP, F32, SIG, TflaError, check, lib_path, load_library, mlstm_bwd, mlstm_fwd,
+                      status_string, workspace_bytes)
+
+__all__ = ["EXP", "SIG", "F32", "BF16", "TflaError", "check", "lib_path", "load_library", "mlstm_fwd",
+           "mlstm_bwd", "status_string", "workspace_bytes"]

@@ -1,0 +1,166 @@
+"""ctypes binding with the same names and argument order as include/tfla_mlstm.h."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+EXP, SIG = 0, 1
+F32, BF16 = 0, 1
+FWD, BWD = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "lib", "libtfla_mlstm.so")
+_lib = None
+
+EXPORTS = ("tfla_mlstm_fwd", "tfla_mlstm_bwd", "tfla_mlstm_workspace_bytes", "tfla_mlstm_check",
+           "tfla_status_string", "tfla_version")
+
+
+class TflaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed with status %d: %s" % (where, status, status_string(status)))
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libtfla_mlstm.so; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libtfla_mlstm.so is missing at %s: build it with "
+                          "`python -m paper_2503_14376_amd.build` (there is no fallback path)" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, fp, ci, cf, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.tfla_mlstm_fwd.restype = ci
+    lib.tfla_mlstm_fwd.argtypes = [vp, vp, vp, fp, fp, fp, fp, fp, ci, ci, ci, ci, ci, ci, ci, ci, cf,
+                                   vp, fp, fp, fp, fp, fp, vp, sz, vp]
+    lib.tfla_mlstm_bwd.restype = ci
+    lib.tfla_mlstm_bwd.argtypes = [vp, vp, vp, fp, fp, fp, fp, fp, fp, fp, vp, fp, ci, ci, ci, ci, ci, ci, ci, ci, cf,
+                                   vp, vp, vp, fp, fp, fp, vp, sz, vp]
+    lib.tfla_mlstm_workspace_bytes.restype = sz
+    lib.tfla_mlstm_workspace_bytes.argtypes = [ci] * 9
+    lib.tfla_mlstm_check.restype = ci
+    lib.tfla_mlstm_check.argtypes = [ci] * 9
+    lib.tfla_status_string.restype = ctypes.c_char_p
+    lib.tfla_status_string.argtypes = [ci]
+    lib.tfla_version.restype = ci
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().tfla_status_string(int(status)).decode()
+
+
+def workspace_bytes(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) -> int:
+    return int(load_library().tfla_mlstm_workspace_bytes(direction, B, NH, T, dqk, dhv, chunk, variant, dtype))
+
+
+def check(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) -> int:
+    return int(load_library().tfla_mlstm_check(direction, B, NH, T, dqk, dhv, chunk, variant, dtype))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _torch_dtype(dtype):
+    import torch
+    return torch.bfloat16 if dtype == BF16 else torch.float32
+
+
+def _stream_handle(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _want(t, dtype, shape, name):
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must be a contiguous device tensor of dtype %s and shape %s (got %s %s)"
+                         % (name, dtype, tuple(shape), t.dtype, tuple(t.shape)))
+
+
+def mlstm_fwd(q, k, v, i_pre, f_pre, C0=None, n0=None, m0=None, chunk=256, variant=EXP, eps=1e-6,
+              return_state=True, workspace=None, stream=None, out: Optional[Dict] = None) -> Dict:
+    """tfla_mlstm_fwd on torch device tensors.  q,k: (B,NH,T,dqk); v: (B,NH,T,dhv) in bf16 or
+    fp32; gates fp32 (B,NH,T).  Returns a dict with H, Cn, nn, mn, n_out, m_out."""
+    import torch
+    lib = load_library()
+    B, NH, T, dqk = q.shape
+    dhv = v.shape[-1]
+    dtype = BF16 if q.dtype == torch.bfloat16 else F32
+    td, f32 = _torch_dtype(dtype), torch.float32
+    _want(q, td, (B, NH, T, dqk), "q"); _want(k, td, (B, NH, T, dqk), "k"); _want(v, td, (B, NH, T, dhv), "v")
+    _want(i_pre, f32, (B, NH, T), "i_pre"); _want(f_pre, f32, (B, NH, T), "f_pre")
+    _want(C0, f32, (B, NH, dqk, dhv), "C0"); _want(n0, f32, (B, NH, dqk), "n0"); _want(m0, f32, (B, NH), "m0")
+    dev = q.device
+    o = out if out is not None else {}
+    if "H" not in o:
+        o["H"] = torch.empty((B, NH, T, dhv), dtype=td, device=dev)
+    if return_state and "Cn" not in o:
+        o["Cn"] = torch.empty((B, NH, dqk, dhv), dtype=f32, device=dev)
+        o["nn"] = torch.empty((B, NH, dqk), dtype=f32, device=dev)
+        o["mn"] = torch.empty((B, NH), dtype=f32, device=dev)
+    if "n_out" not in o:
+        o["n_out"] = torch.empty((B, NH, T), dtype=f32, device=dev)
+        o["m_out"] = torch.empty((B, NH, T), dtype=f32, device=dev)
+    need = workspace_bytes(FWD, B, NH, T, dqk, dhv, chunk, variant, dtype)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    rc = lib.tfla_mlstm_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(i_pre), _ptr(f_pre), _ptr(C0), _ptr(n0), _ptr(m0),
+                            B, NH, T, dqk, dhv, int(chunk), int(variant), dtype, float(eps),
+                            _ptr(o["H"]), _ptr(o.get("Cn")), _ptr(o.get("nn")), _ptr(o.get("mn")),
+                            _ptr(o["n_out"]), _ptr(o["m_out"]),
+                            _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream_handle(stream))
+    if rc != 0:
+        raise TflaError(rc, "tfla_mlstm_fwd")
+    o["workspace"] = workspace
+    return o
+
+
+def mlstm_bwd(q, k, v, i_pre, f_pre, dH, n_out=None, m_out=None, C0=None, n0=None, m0=None, dCn=None,
+              chunk=256, variant=EXP, eps=1e-6, want_dC0=True, workspace=None, stream=None,
+              out: Optional[Dict] = None) -> Dict:
+    """tfla_mlstm_bwd on torch device tensors.  Returns dq, dk, dv, d_i_pre, d_f_pre, dC0."""
+    import torch
+    lib = load_library()
+    B, NH, T, dqk = q.shape
+    dhv = v.shape[-1]
+    dtype = BF16 if q.dtype == torch.bfloat16 else F32
+    td, f32 = _torch_dtype(dtype), torch.float32
+    _want(q, td, (B, NH, T, dqk), "q"); _want(k, td, (B, NH, T, dqk), "k"); _want(v, td, (B, NH, T, dhv), "v")
+    _want(dH, td, (B, NH, T, dhv), "dH")
+    _want(i_pre, f32, (B, NH, T), "i_pre"); _want(f_pre, f32, (B, NH, T), "f_pre")
+    _want(n_out, f32, (B, NH, T), "n_out"); _want(m_out, f32, (B, NH, T), "m_out")
+    _want(C0, f32, (B, NH, dqk, dhv), "C0"); _want(n0, f32, (B, NH, dqk), "n0"); _want(m0, f32, (B, NH), "m0")
+    _want(dCn, f32, (B, NH, dqk, dhv), "dCn")
+    dev = q.device
+    o = out if out is not None else {}
+    if "dq" not in o:
+        o["dq"] = torch.empty_like(q); o["dk"] = torch.empty_like(k); o["dv"] = torch.empty_like(v)
+        o["d_i_pre"] = torch.empty((B, NH, T), dtype=f32, device=dev)
+        o["d_f_pre"] = torch.empty((B, NH, T), dtype=f32, device=dev)
+    if want_dC0 and "dC0" not in o:
+        o["dC0"] = torch.empty((B, NH, dqk, dhv), dtype=f32, device=dev)
+    need = workspace_bytes(BWD, B, NH, T, dqk, dhv, chunk, variant, dtype)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    rc = lib.tfla_mlstm_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(i_pre), _ptr(f_pre), _ptr(C0), _ptr(n0), _ptr(m0),
+                            _ptr(n_out), _ptr(m_out), _ptr(dH), _ptr(dCn),
+                            B, NH, T, dqk, dhv, int(chunk), int(variant), dtype, float(eps),
+                            _ptr(o["dq"]), _ptr(o["dk"]), _ptr(o["dv"]), _ptr(o["d_i_pre"]), _ptr(o["d_f_pre"]),
+                            _ptr(o.get("dC0")),
+                            _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream_handle(stream))
+    if rc != 0:
+        raise TflaError(rc, "tfla_mlstm_bwd")
+    o["workspace"] = workspace
+    return o

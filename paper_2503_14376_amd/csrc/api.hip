@@ -1,0 +1,270 @@
+// C ABI of libtfla_mlstm: argument validation, workspace layout and the kernel sequence of
+// the forward and backward pass.  See include/tfla_mlstm.h for the contract.
+#include "../../include/tfla_mlstm.h"
+#include "tfla_internal.h"
+
+#include <math.h>
+
+using namespace tfla;
+
+namespace {
+
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Dims {
+    int B, NH, T, dqk, dhv, L, variant, dtype;
+    long BH, BHT;
+    int Nc;
+    size_t esz;
+};
+
+int check_dims(int direction, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype) {
+    if (direction != TFLA_FWD && direction != TFLA_BWD) return TFLA_ERR_ENUM;
+    if (variant != TFLA_EXP && variant != TFLA_SIG) return TFLA_ERR_ENUM;
+    if (dtype != TFLA_F32 && dtype != TFLA_BF16) return TFLA_ERR_ENUM;
+    if (B <= 0 || NH <= 0 || T <= 0 || dqk <= 0 || dhv <= 0) return TFLA_ERR_SHAPE;
+    const int dmax = dtype == TFLA_BF16 ? 512 : 256;
+    auto ok_d = [&](int d) { return (d == 64 || d == 128 || d == 256 || d == 512) && d <= dmax; };
+    if (!ok_d(dqk) || !ok_d(dhv)) return TFLA_ERR_SHAPE;
+    if ((long)B * NH > 65535) return TFLA_ERR_SHAPE;
+    if (chunk < 64 || chunk > 2048 || chunk % 64 != 0 || T % chunk != 0) return TFLA_ERR_CHUNK;
+    if (T / chunk > 4096) return TFLA_ERR_CHUNK;
+    if ((long)B * NH * (T / chunk) > 2147483647L / 2) return TFLA_ERR_SHAPE;
+    return TFLA_OK;
+}
+
+Dims make_dims(int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype) {
+    Dims d;
+    d.B = B; d.NH = NH; d.T = T; d.dqk = dqk; d.dhv = dhv; d.L = chunk; d.variant = variant; d.dtype = dtype;
+    d.BH = (long)B * NH; d.BHT = d.BH * T; d.Nc = T / chunk;
+    d.esz = dtype == TFLA_BF16 ? 2 : 4;
+    return d;
+}
+
+// Bump allocator over the caller's workspace.
+struct Carver {
+    char* base; size_t off;
+    explicit Carver(void* p) : base(reinterpret_cast<char*>(p)), off(0) {}
+    template <typename T> T* take(size_t count) {
+        T* r = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off = align_up(off + count * sizeof(T));
+        return r;
+    }
+    void* take_bytes(size_t bytes) {
+        void* r = base ? base + off : nullptr;
+        off = align_up(off + bytes);
+        return r;
+    }
+};
+
+struct FwdWs {
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *nst;
+    void* stT;
+    size_t bytes;
+};
+FwdWs carve_fwd(const Dims& d, void* ws) {
+    Carver c(ws);
+    FwdWs w;
+    w.wrow = c.take<float>(d.BHT); w.ucol = c.take<float>(d.BHT); w.sH = c.take<float>(d.BHT);
+    w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
+    w.gbar = c.take<float>(d.BH * d.Nc);
+    w.nst = c.take<float>(d.BH * d.Nc * d.dqk);
+    w.stT = c.take_bytes((size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz);
+    w.bytes = c.off;
+    return w;
+}
+
+struct BwdWs {
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal;
+    void *cN, *dcT, *dcN;
+    int nbQ, nbK;
+    size_t bytes;
+};
+BwdWs carve_bwd(const Dims& d, void* ws) {
+    Carver c(ws);
+    BwdWs w;
+    w.wrow = c.take<float>(d.BHT); w.ucol = c.take<float>(d.BHT); w.sH = c.take<float>(d.BHT);
+    w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
+    w.gbar = c.take<float>(d.BH * d.Nc);
+    w.wrowB = c.take<float>(d.BHT); w.sQ = c.take<float>(d.BHT);
+    w.nbQ = d.dqk / tile_bd2(d.L, d.dqk, d.dtype);
+    w.nbK = w.nbQ;
+    w.partQ = c.take<float>((size_t)w.nbQ * d.BHT); w.partK = c.take<float>((size_t)w.nbK * d.BHT);
+    w.cdot = c.take<float>(d.BH);
+    w.Cfinal = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
+    const size_t st = (size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz;
+    w.cN = c.take_bytes(st); w.dcT = c.take_bytes(st); w.dcN = c.take_bytes(st);
+    w.bytes = c.off;
+    return w;
+}
+
+#define TFLA_TRY(expr)                         \
+    do {                                       \
+        hipError_t e_ = (expr);                \
+        if (e_ != hipSuccess) return (int)e_;  \
+    } while (0)
+
+int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float* m0, float* wrow, float* ucol,
+              float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, hipStream_t s) {
+    GateArgs g;
+    g.i_pre = i_pre; g.f_pre = f_pre; g.m0 = d.variant == TFLA_EXP ? m0 : nullptr;
+    g.T = d.T; g.L = d.L; g.Nc = d.Nc; g.variant = d.variant;
+    g.qscale = 1.0f / sqrtf((float)d.dqk);
+    g.wrow = wrow; g.ucol = ucol; g.sH = sH; g.aK = aK; g.gbar = gbar; g.mout = mout; g.mfinal = mfinal; g.tmp = tmp;
+    TFLA_TRY(launch_gates(g, (int)d.BH, s));
+    return TFLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tfla_version(void) { return 1000; }
+
+const char* tfla_status_string(int status) {
+    switch (status) {
+        case TFLA_OK: return "ok";
+        case TFLA_ERR_NULL: return "a required pointer is NULL";
+        case TFLA_ERR_SHAPE: return "invalid or unsupported dimension";
+        case TFLA_ERR_CHUNK: return "chunk must be a multiple of 64 in [64, 2048] that divides T (T/chunk <= 4096)";
+        case TFLA_ERR_ENUM: return "unknown variant, dtype or direction";
+        case TFLA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
+        case TFLA_ERR_STATE: return "initial state must be given completely (C0, n0, m0) or not at all";
+        default: break;
+    }
+    if (status > 0) return hipGetErrorString((hipError_t)status);
+    return "unknown status";
+}
+
+int tfla_mlstm_check(int direction, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype) {
+    return check_dims(direction, B, NH, T, dqk, dhv, chunk, variant, dtype);
+}
+
+size_t tfla_mlstm_workspace_bytes(int direction, int B, int NH, int T, int dqk, int dhv, int chunk, int variant,
+                                  int dtype) {
+    if (check_dims(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) != TFLA_OK) return 0;
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    return direction == TFLA_FWD ? carve_fwd(d, nullptr).bytes : carve_bwd(d, nullptr).bytes;
+}
+
+int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                   const float* C0, const float* n0, const float* m0, int B, int NH, int T, int dqk, int dhv,
+                   int chunk, int variant, int dtype, float eps, void* H, float* Cn, float* nn, float* mn,
+                   float* n_out, float* m_out, void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (rc != TFLA_OK) return rc;
+    if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
+    if (variant == TFLA_EXP) {
+        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
+        if (given != 0 && given != 3) return TFLA_ERR_STATE;
+    }
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+    const FwdWs w = carve_fwd(d, workspace);
+    if (workspace_bytes < w.bytes) return TFLA_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const bool is_exp = variant == TFLA_EXP;
+
+    // 1. gates, max states
+    float* mout = (is_exp && m_out) ? m_out : w.mout;
+    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, s);
+    if (st != TFLA_OK) return st;
+
+    // 2. recurrent kernel: C_{k-1} (transposed, element type of q/k/v) and n_{k-1} for every chunk
+    RecArgs r;
+    r.X = k; r.Y = v; r.rs = w.aK; r.gbar = w.gbar; r.S0 = C0;
+    r.stT = w.stT; r.stN = nullptr; r.Sfinal = Cn;
+    r.n0 = is_exp ? n0 : nullptr; r.nst = is_exp ? w.nst : nullptr; r.nfinal = is_exp ? nn : nullptr;
+    r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
+    TFLA_TRY(launch_recurrent(r, (int)d.BH, dtype, s));
+
+    // 3. parallel kernel
+    TileArgs t;
+    t.X = q; t.Y = k; t.Z = v; t.Out = H;
+    t.wrow = w.wrow; t.wcol = w.ucol; t.srow = w.sH; t.St = w.stT;
+    t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
+    t.variant = variant; t.eps = eps; t.nstate = w.nst; t.mout = mout; t.nout = is_exp ? n_out : nullptr;
+    t.dotwith = nullptr; t.dotpart = nullptr;
+    TFLA_TRY(launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
+
+    if (!is_exp) {
+        if (nn) TFLA_TRY(launch_fill_zero(nn, d.BH * dqk, s));
+        if (mn) TFLA_TRY(launch_fill_zero(mn, d.BH, s));
+        if (n_out) TFLA_TRY(launch_fill_zero(n_out, d.BHT, s));
+        if (m_out) TFLA_TRY(launch_fill_zero(m_out, d.BHT, s));
+    }
+    return TFLA_OK;
+}
+
+int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                   const float* C0, const float* n0, const float* m0, const float* n_out, const float* m_out,
+                   const void* dH, const float* dCn, int B, int NH, int T, int dqk, int dhv, int chunk,
+                   int variant, int dtype, float eps, void* dq, void* dk, void* dv, float* d_i_pre,
+                   float* d_f_pre, float* dC0, void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (rc != TFLA_OK) return rc;
+    if (!q || !k || !v || !i_pre || !f_pre || !dH || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
+    const bool is_exp = variant == TFLA_EXP;
+    if (is_exp) {
+        if (!n_out || !m_out) return TFLA_ERR_NULL;
+        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
+        if (given != 0 && given != 3) return TFLA_ERR_STATE;
+    }
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+    const BwdWs w = carve_bwd(d, workspace);
+    if (workspace_bytes < w.bytes) return TFLA_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    // 1. gates as in the forward pass, then fold 1/h_denom into the backward weights
+    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, s);
+    if (st != TFLA_OK) return st;
+    GateBwdPrepArgs p;
+    p.wrow = w.wrow; p.sH = w.sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
+    p.n = d.BHT; p.variant = variant; p.eps = eps;
+    TFLA_TRY(launch_gate_bwd_prep(p, s));
+
+    // 2. recompute the chunk states C_{k-1} (layout d_qk x d_hv, read by the dQ kernel)
+    RecArgs r;
+    r.X = k; r.Y = v; r.rs = w.aK; r.gbar = w.gbar; r.S0 = C0;
+    r.stT = nullptr; r.stN = w.cN; r.Sfinal = dCn ? w.Cfinal : nullptr;
+    r.n0 = nullptr; r.nst = nullptr; r.nfinal = nullptr;
+    r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
+    TFLA_TRY(launch_recurrent(r, (int)d.BH, dtype, s));
+
+    // 3. backward recurrence: dC_k for every chunk (both layouts), dC_0 at the end
+    RecArgs rb;
+    rb.X = q; rb.Y = dH; rb.rs = w.sQ; rb.gbar = w.gbar; rb.S0 = dCn;
+    rb.stT = w.dcT; rb.stN = w.dcN; rb.Sfinal = dC0;
+    rb.n0 = nullptr; rb.nst = nullptr; rb.nfinal = nullptr;
+    rb.T = T; rb.L = chunk; rb.Nc = d.Nc; rb.d1 = dqk; rb.d2 = dhv; rb.reverse = 1;
+    TFLA_TRY(launch_recurrent(rb, (int)d.BH, dtype, s));
+
+    // 4. the three gradient kernels
+    TileArgs t;
+    t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
+    t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr;
+    // dV: rows = kv index j
+    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = w.ucol; t.wcol = w.wrowB; t.srow = w.aK; t.St = w.dcT;
+    t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
+    TFLA_TRY(launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
+    // dQ: rows = query index i
+    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = w.wrowB; t.wcol = w.ucol; t.srow = w.sQ; t.St = w.cN;
+    t.d1 = dhv; t.d2 = dqk; t.dotwith = q; t.dotpart = w.partQ;
+    TFLA_TRY(launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
+    // dK: rows = kv index j
+    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = w.ucol; t.wcol = w.wrowB; t.srow = w.aK; t.St = w.dcN;
+    t.d1 = dhv; t.d2 = dqk; t.dotwith = k; t.dotpart = w.partK;
+    TFLA_TRY(launch_tile_mode<MODE_DK>(t, (int)d.BH, dtype, s));
+
+    // 5. gate gradients
+    if (dCn) TFLA_TRY(launch_state_dot(w.Cfinal, dCn, w.cdot, (long)dqk * dhv, (int)d.BH, s));
+    GateGradArgs gg;
+    gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
+    gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
+    gg.BHT = d.BHT;
+    TFLA_TRY(launch_gate_grads(gg, (int)d.BH, s));
+    return TFLA_OK;
+}
+
+}  // extern "C"

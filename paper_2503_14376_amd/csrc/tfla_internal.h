@@ -1,0 +1,96 @@
+// Host-side declarations shared by the translation units of libtfla_mlstm: argument blocks
+// of the kernel families and their launchers.  Nothing here is exported.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace tfla {
+
+// ---- chunkwise gates (App. B.2 "Chunkwise Gates", App. B.2 inter-chunk max state) ----------
+struct GateArgs {
+    const float* i_pre;   // (BH, T)
+    const float* f_pre;   // (BH, T)
+    const float* m0;      // (BH) or NULL
+    int T, L, Nc, variant;
+    float qscale;         // 1/sqrt(dqk)
+    // outputs, all (BH, T) unless noted
+    float* wrow;          // log2-domain row term of the intra-chunk weight (includes log2 qscale)
+    float* ucol;          // log2-domain column term (i-bar_j - b_j) * log2(e)
+    float* sH;            // inter-chunk row scale b-bar_i * qscale
+    float* aK;            // a-bar_j = exp(a_j - m_k)
+    float* gbar;          // (BH, Nc) g-bar_k
+    float* mout;          // combined max state m_t of every step
+    float* mfinal;        // (BH) m after the last chunk, or NULL
+    float* tmp;           // (BH, 3, T) scratch
+};
+hipError_t launch_gates(const GateArgs& a, int BH, hipStream_t s);
+
+struct GateBwdPrepArgs {
+    const float* wrow; const float* sH; const float* n_out; const float* m_out;
+    float* wrowB; float* sQ;
+    long n; int variant; float eps;
+};
+hipError_t launch_gate_bwd_prep(const GateBwdPrepArgs& a, hipStream_t s);
+
+struct GateGradArgs {
+    const float* partQ; int nbQ;   // (nbQ, BH*T) partial q.dq
+    const float* partK; int nbK;   // (nbK, BH*T) partial k.dk
+    const float* cdot;             // (BH) <C_T, dC_T> or NULL
+    const float* i_pre; const float* f_pre;
+    float* d_i; float* d_f;
+    int T, variant; long BHT;
+};
+hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
+
+hipError_t launch_fill_zero(float* p, long n, hipStream_t s);
+hipError_t launch_state_dot(const float* A, const float* Bm, float* out, long per, int BH, hipStream_t s);
+
+// ---- inter-chunk recurrence (App. B.2 "Inter-chunk Recurrent Contribution"; App. B.3) -------
+// state <- gbar[k] * state + (rs (.) X_k)^T Y_k, chunk by chunk; the state *before* each
+// update is written to slot k.
+struct RecArgs {
+    const void* X;        // (BH, T, d1)
+    const void* Y;        // (BH, T, d2)
+    const float* rs;      // (BH, T)
+    const float* gbar;    // (BH, Nc)
+    const float* S0;      // (BH, d1, d2) fp32 or NULL (zero)
+    void* stT;            // (BH, Nc, d2, d1) element type DT, or NULL
+    void* stN;            // (BH, Nc, d1, d2) element type DT, or NULL
+    float* Sfinal;        // (BH, d1, d2) fp32 or NULL
+    const float* n0;      // (BH, d1) or NULL; normaliser vector, forward mLSTMexp only
+    float* nst;           // (BH, Nc, d1) or NULL (NULL = no normaliser vector)
+    float* nfinal;        // (BH, d1) or NULL
+    int T, L, Nc, d1, d2, reverse;
+};
+hipError_t launch_recurrent(const RecArgs& a, int BH, int dtype, hipStream_t s);
+
+// ---- intra-chunk tiled kernels (Sec. 3, App. C.3 Alg. 1, App. C.4) ---------------------------
+// out[r,:] = sum_c exp2(wrow[r] + wcol[c]) * (X_r . Y_c) * Z_c  (causal within the chunk)
+//            + srow[r] * (X_r St)
+enum { MODE_H = 0, MODE_DV = 1, MODE_DQ = 2, MODE_DK = 3 };
+struct TileArgs {
+    const void* X; const void* Y;   // (BH, T, d1)
+    const void* Z; void* Out;       // (BH, T, d2)
+    const float* wrow; const float* wcol; const float* srow;   // (BH, T)
+    const void* St;                 // (BH, Nc, d2, d1)
+    int T, L, Nc, d1, d2;
+    // MODE_H, mLSTMexp: normaliser
+    int variant; float eps;
+    const float* nstate;            // (BH, Nc, d1)
+    const float* mout;              // (BH, T)
+    float* nout;                    // (BH, T) or NULL
+    // MODE_DQ / MODE_DK: partial row dots  sum_n out[r,n] * dotwith[r,n]
+    const void* dotwith;            // (BH, T, d2)
+    float* dotpart;                 // (d2/BD2, BH*T)
+};
+template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
+// d2 block of a tiled kernel: as wide as the register budget allows (256 for bf16 with
+// 128-row workgroups)
+inline int tile_bd2(int L, int d2, int dtype) {
+    const bool wide = dtype == 1 && (L % 128 == 0);
+    if (wide && d2 % 256 == 0) return 256;
+    if (d2 % 128 == 0) return 128;
+    return 64;
+}
+
+}  // namespace tfla

@@ -1,0 +1,244 @@
+// Intra-chunk tiled kernel (paper Sec. 3; App. C.3 Alg. 1 for H; App. C.4 for the three
+// gradient kernels, with the parallel / loop dimensions of the paper's parallelisation table).
+//
+// One template covers the four kernels.  For a block of output rows r of one chunk:
+//
+//   out[r, :] = sum_{c causal} exp2(wrow[r] + wcol[c]) * (X_r . Y_c) * Z_c  +  srow[r] * (X_r St)
+//
+//   H   : X=Q  Y=K  Z=V   St=C_{k-1}^T        c <= r      (Alg. 1, both parts in one accumulator)
+//   dV  : X=K  Y=Q  Z=dH  St=dC_k^T           c >= r
+//   dQ  : X=dH Y=V  Z=K   St=C_{k-1}          c <= r
+//   dK  : X=V  Y=dH Z=Q   St=dC_k             c >= r
+//
+// Differences from Alg. 1: the max state of every row is known from the gates alone (see the
+// gate kernel), so the weights are final when they are formed -- no running maximum, no
+// rescaling of the accumulator, and the inter-chunk product shares the accumulator and the
+// register-resident X fragments with the intra-chunk loop for mLSTMexp as well.
+//
+// Work split: grid = (d2 / BD2, L / (32*NW), B*NH*Nc).  A wavefront owns 32 output rows and
+// all BD2 columns of its workgroup; X_r stays in registers for the whole kernel; Y tiles
+// (natural) and Z tiles (transposed, k-permuted) go through LDS and are shared by the
+// waves.  The product (X_r . Y_c) is formed transposed (rows = c) so that its MFMA result is
+// already laid out as the A operand of the second product.
+#include "tfla_device.h"
+#include "tfla_internal.h"
+
+namespace tfla {
+
+template <typename DT, int D1, int BD2, int BC, int NW, int MODE>
+__global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
+    using E = Elem<DT>;
+    using frag = typename E::frag;
+    constexpr bool UPPER = (MODE & 1) != 0;
+    constexpr int NT = NW * 64, BR = NW * 32;
+    constexpr int KS1 = D1 / 16, NB = BD2 / 32;
+    constexpr int YS = D1 + E::PAD, ZS = BC + E::PAD;
+    __shared__ __attribute__((aligned(16))) DT ldsY[BC * YS];
+    __shared__ __attribute__((aligned(16))) DT ldsZ[BD2 * ZS];
+    __shared__ float ldsW[BC];
+    __shared__ float ldsR[NW * 32];
+    __shared__ float ldsN[(MODE == MODE_H) ? D1 : 1];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int nb2 = blockIdx.x, rb = blockIdx.y;
+    const int kc = blockIdx.z % a.Nc, bh = blockIdx.z / a.Nc;
+    const long tbase = (long)bh * a.T + (long)kc * a.L;   // first step of the chunk
+    const int r0 = rb * BR;                               // chunk-local first row of the workgroup
+    const int wr0 = r0 + wave * 32;                       // ... of the wavefront
+    const int d2 = a.d2;
+
+    const DT* X = reinterpret_cast<const DT*>(a.X);
+    const DT* Y = reinterpret_cast<const DT*>(a.Y);
+    const DT* Z = reinterpret_cast<const DT*>(a.Z);
+
+    // X fragments of the wavefront's 32 rows (lane: row l32, k-group g)
+    frag xf[KS1];
+    {
+        const DT* xr = X + (tbase + wr0 + l32) * D1 + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks) xf[ks] = E::load(xr + 16 * ks);
+    }
+
+    f32x16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+
+    // ---------------- inter-chunk part: acc = X_r St, BC columns of d1 at a time
+    {
+        const DT* St = reinterpret_cast<const DT*>(a.St) + (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * D1;
+#pragma unroll
+        for (int kk = 0; kk < D1; kk += BC) {
+            __syncthreads();
+            stage_rows<DT, BD2, BC, NT>(ldsZ, ZS, St + kk, D1, tid);
+            __syncthreads();
+#pragma unroll
+            for (int ks = 0; ks < BC / 16; ++ks) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const frag b = E::load(ldsZ + (nb * 32 + l32) * ZS + 16 * ks + 8 * g);
+                    acc[nb] = E::mma(xf[kk / 16 + ks], b, acc[nb]);
+                }
+            }
+        }
+        float sr[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sr[v] = a.srow[tbase + wr0 + acc_row(v, g)];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][v] *= sr[v];
+    }
+
+    // mLSTMexp normaliser, inter-chunk part: srow_i * (q_i . n_{k-1}), one value per row
+    float nrm = 0.0f;
+    if (MODE == MODE_H) {
+        if (a.variant == 0) {
+            __syncthreads();
+            for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * D1 + i];
+            __syncthreads();
+            float dot = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot += E::frag_elem(xf[ks], e) * ldsN[16 * ks + 8 * g + e];
+            dot += __shfl_xor(dot, 32, 64);
+            nrm = dot * a.srow[tbase + wr0 + l32];
+        }
+    }
+
+    // ---------------- intra-chunk part
+    const float wr = a.wrow[tbase + wr0 + l32];
+    float rowsum = 0.0f;
+    const int ct_lo = UPPER ? r0 / BC : 0;
+    const int ct_hi = UPPER ? a.L / BC : (r0 + BR) / BC;
+    for (int ct = ct_lo; ct < ct_hi; ++ct) {
+        const int c0 = ct * BC;
+        __syncthreads();
+        stage_rows<DT, BC, D1, NT>(ldsY, YS, Y + (tbase + c0) * D1, D1, tid);
+        stage_transposed<BC, BD2, NT, true, false>(ldsZ, ZS, Z + (tbase + c0) * d2 + (long)nb2 * BD2, d2, nullptr, tid);
+        if (tid < BC) ldsW[tid] = a.wcol[tbase + c0 + tid];
+        __syncthreads();
+#pragma unroll
+        for (int st = 0; st < BC / 32; ++st) {
+            const int cs = c0 + 32 * st;
+            if (UPPER ? (cs + 31 < wr0) : (cs > wr0 + 31)) continue;      // fully masked for this wave
+            const bool diag = UPPER ? (cs < wr0 + 31) : (cs + 31 > wr0);
+            f32x16 s;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[v] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) {
+                const frag ya = E::load(ldsY + (32 * st + l32) * YS + 16 * ks + 8 * g);
+                s = E::mma(ya, xf[ks], s);
+            }
+            float p[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int cl = acc_row(v, g);
+                float w = fast_exp2(wr + ldsW[32 * st + cl]);
+                if (diag) {
+                    const bool keep = UPPER ? (cs + cl >= wr0 + l32) : (cs + cl <= wr0 + l32);
+                    w = keep ? w : 0.0f;
+                }
+                p[v] = s[v] * w;
+                rowsum += p[v];
+            }
+            const frag p0 = E::pack(p), p1 = E::pack(p + 8);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const DT* zrow = ldsZ + (nb * 32 + l32) * ZS + 32 * st + 8 * g;
+                acc[nb] = E::mma(p0, E::load(zrow), acc[nb]);
+                acc[nb] = E::mma(p1, E::load(zrow + 16), acc[nb]);
+            }
+        }
+    }
+
+    // ---------------- epilogue
+    float inv[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) inv[v] = 1.0f;
+    if (MODE == MODE_H) {
+        if (a.variant == 0) {
+            rowsum += __shfl_xor(rowsum, 32, 64);
+            nrm += rowsum;
+            const long t = tbase + wr0 + l32;
+            const float den = fmaxf(fabsf(nrm), expf(-a.mout[t])) + a.eps;
+            if (g == 0) {
+                ldsR[wave * 32 + l32] = 1.0f / den;
+                if (a.nout && nb2 == 0) a.nout[t] = nrm;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) inv[v] = ldsR[wave * 32 + acc_row(v, g)];
+        }
+    }
+    DT* Out = reinterpret_cast<DT*>(a.Out);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const long t = tbase + wr0 + acc_row(v, g);
+            Out[t * d2 + (long)nb2 * BD2 + nb * 32 + l32] = E::from_f32(acc[nb][v] * inv[v]);
+        }
+    if (MODE == MODE_DQ || MODE == MODE_DK) {
+        const DT* W = reinterpret_cast<const DT*>(a.dotwith);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const long t = tbase + wr0 + acc_row(v, g);
+            float d = 0.0f;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                d += acc[nb][v] * E::to_f32(W[t * d2 + (long)nb2 * BD2 + nb * 32 + l32]);
+            d = half_sum(d);
+            if (l32 == 0) a.dotpart[(long)nb2 * ((long)gridDim.z / a.Nc) * a.T + t] = d;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+template <typename DT, int D1, int BD2, int NW, int MODE>
+static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
+    constexpr int BC = sizeof(DT) == 2 ? 64 : 32;
+    dim3 grid(a.d2 / BD2, a.L / (32 * NW), BH * a.Nc);
+    hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE>), grid, dim3(64 * NW), 0, s, a);
+    return hipGetLastError();
+}
+
+template <typename DT, int D1, int MODE>
+static hipError_t launch_tile_d1(const TileArgs& a, int BH, int bd2, hipStream_t s) {
+    if (a.L % 128 == 0) {
+        if (sizeof(DT) == 2 && bd2 == 256) return launch_tile_t<DT, D1, (sizeof(DT) == 2 ? 256 : 128), 4, MODE>(a, BH, s);
+        if (bd2 == 128) return launch_tile_t<DT, D1, 128, 4, MODE>(a, BH, s);
+        return launch_tile_t<DT, D1, 64, 4, MODE>(a, BH, s);
+    }
+    if (bd2 == 128) return launch_tile_t<DT, D1, 128, 2, MODE>(a, BH, s);
+    return launch_tile_t<DT, D1, 64, 2, MODE>(a, BH, s);
+}
+
+template <typename DT, int MODE>
+static hipError_t launch_tile_m(const TileArgs& a, int BH, int bd2, hipStream_t s) {
+    switch (a.d1) {
+        case 64: return launch_tile_d1<DT, 64, MODE>(a, BH, bd2, s);
+        case 128: return launch_tile_d1<DT, 128, MODE>(a, BH, bd2, s);
+        case 256: return launch_tile_d1<DT, 256, MODE>(a, BH, bd2, s);
+        case 512:
+            if (sizeof(DT) == 2) return launch_tile_d1<DT, (sizeof(DT) == 2 ? 512 : 64), MODE>(a, BH, bd2, s);
+            break;
+        default: break;
+    }
+    return hipErrorInvalidValue;
+}
+
+template <int MODE>
+hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s) {
+    const int bd2 = tile_bd2(a.L, a.d2, dtype);
+    return dtype == 1 ? launch_tile_m<bf16_t, MODE>(a, BH, bd2, s) : launch_tile_m<float, MODE>(a, BH, bd2, s);
+}
+
+// One translation unit per (mode, element type) keeps compile times parallel: tile_inst.hip
+// is compiled once for every TFLA_TILE_MODE.
+template hipError_t launch_tile_mode<TFLA_TILE_MODE>(const TileArgs&, int, int, hipStream_t);
+
+}  // namespace tfla

@@ -1,0 +1,6 @@
+// Compiled once per TFLA_TILE_MODE (0 = H, 1 = dV, 2 = dQ, 3 = dK): instantiates the tiled
+// kernel family of that mode.  The mode is given on the compiler command line.
+#ifndef TFLA_TILE_MODE
+#error "compile with -DTFLA_TILE_MODE=<0..3>"
+#endif
+#include "tile.hip"
