@@ -27,7 +27,8 @@
  *    nn, mn, n_out, m_out are filled with zeros when non-NULL.
  *  - eps is added to the denominator max{|n^T q~|, exp(-m)}; eps = 0 is the paper's formula.
  *  - Restrictions: T % chunk == 0, chunk % 64 == 0, 64 <= chunk <= 2048,
- *    T / chunk <= 4096, dqk and dhv multiples of 64 and <= 512 (<= 256 for TFLA_F32).
+ *    T / chunk <= 4096, dqk and dhv in {64, 128, 256, 512} (at most 256 for TFLA_F32),
+ *    B * NH <= 65535.
  *  - Return value: TFLA_OK (0) on success; a negative TFLA_ERR_* code for an invalid
  *    argument (checked before anything is launched, nothing is written); a positive value is
  *    the hipError_t of a failed launch.  No entry point throws or aborts.
@@ -120,6 +121,20 @@ TFLA_API int tfla_mlstm_check(int direction, int B, int NH, int T, int dqk, int 
 
 /* Human-readable text for a status code (static storage). */
 TFLA_API const char* tfla_status_string(int status);
+
+/*
+ * Optional per-kernel timing (host functions; not thread-safe; process-wide state).
+ * tfla_profile_enable(n > 0) creates n pairs of HIP events and makes every kernel launch of
+ * the two entry points record one pair on the caller's stream until n launches have been
+ * recorded since the last read; tfla_profile_enable(0) switches timing off and destroys the
+ * events.  tfla_profile_read synchronises on the recorded events, adds their elapsed times to
+ * the per-kernel totals and returns the totals of kernel family `kernel`
+ * (0 <= kernel < tfla_profile_kernels()); name receives the family's name (NUL-terminated).
+ * These are the only entry points that create HIP objects; tfla_mlstm_fwd/bwd never do.
+ */
+TFLA_API int tfla_profile_enable(int max_launches);
+TFLA_API int tfla_profile_read(int kernel, char* name, int name_len, double* total_ms, long* launches);
+TFLA_API int tfla_profile_kernels(void);
 
 /* Library version, major * 1000 + minor. */
 TFLA_API int tfla_version(void);

@@ -6,7 +6,7 @@ for device memory and streams.  There is no CPU or eager fallback: if the librar
 been built (python -m paper_2503_14376_amd.build) importing the binding fails loudly.
 """
 from .binding import (BF16, EXP, F32, SIG, TflaError, check, lib_path, load_library, mlstm_bwd, mlstm_fwd,
-                      status_string, workspace_bytes)
+                      profile_enable, profile_read, status_string, workspace_bytes)
 
 __all__ = ["EXP", "SIG", "F32", "BF16", "TflaError", "check", "lib_path", "load_library", "mlstm_fwd",
-           "mlstm_bwd", "status_string", "workspace_bytes"]
+           "mlstm_bwd", "profile_enable", "profile_read", "status_string", "workspace_bytes"]

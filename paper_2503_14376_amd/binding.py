@@ -14,7 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "lib", "libtfla_mlstm.so")
 _lib = None
 
 EXPORTS = ("tfla_mlstm_fwd", "tfla_mlstm_bwd", "tfla_mlstm_workspace_bytes", "tfla_mlstm_check",
-           "tfla_status_string", "tfla_version")
+           "tfla_status_string", "tfla_version", "tfla_profile_enable", "tfla_profile_read",
+           "tfla_profile_kernels")
 
 
 class TflaError(RuntimeError):
@@ -50,6 +51,12 @@ def load_library():
     lib.tfla_status_string.restype = ctypes.c_char_p
     lib.tfla_status_string.argtypes = [ci]
     lib.tfla_version.restype = ci
+    lib.tfla_profile_enable.restype = ci
+    lib.tfla_profile_enable.argtypes = [ci]
+    lib.tfla_profile_read.restype = ci
+    lib.tfla_profile_read.argtypes = [ci, ctypes.c_char_p, ci, ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_long)]
+    lib.tfla_profile_kernels.restype = ci
     _lib = lib
     return lib
 
@@ -64,6 +71,24 @@ def workspace_bytes(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) -> int
 
 def check(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) -> int:
     return int(load_library().tfla_mlstm_check(direction, B, NH, T, dqk, dhv, chunk, variant, dtype))
+
+
+def profile_enable(max_launches: int) -> None:
+    rc = load_library().tfla_profile_enable(int(max_launches))
+    if rc != 0:
+        raise TflaError(rc, "tfla_profile_enable")
+
+
+def profile_read() -> Dict[str, Dict[str, float]]:
+    """Per-kernel-family totals since tfla_profile_enable: {name: {ms, launches}}."""
+    lib = load_library()
+    out = {}
+    for kidx in range(lib.tfla_profile_kernels()):
+        name = ctypes.create_string_buffer(64)
+        ms, n = ctypes.c_double(0.0), ctypes.c_long(0)
+        lib.tfla_profile_read(kidx, name, 64, ctypes.byref(ms), ctypes.byref(n))
+        out[name.value.decode()] = {"ms": ms.value, "launches": n.value}
+    return out
 
 
 def _ptr(t):

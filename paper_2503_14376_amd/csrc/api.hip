@@ -104,6 +104,54 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
         if (e_ != hipSuccess) return (int)e_;  \
     } while (0)
 
+// ---- optional per-kernel timing with HIP events on the caller's stream -------------------
+enum { K_GATES = 0, K_BWD_PREP, K_REC_FWD, K_REC_BWD, K_TILE_H, K_TILE_DV, K_TILE_DQ, K_TILE_DK, K_GATE_GRADS,
+       K_STATE_DOT, K_FILL, K_COUNT };
+const char* const kKernelNames[K_COUNT] = {"gates", "gate_bwd_prep", "recurrent_fwd", "recurrent_bwd", "tile_H",
+                                           "tile_dV", "tile_dQ", "tile_dK", "gate_grads", "state_dot", "fill_zero"};
+struct Profiler {
+    bool on = false;
+    int cap = 0, used = 0;
+    hipEvent_t* beg = nullptr;
+    hipEvent_t* end = nullptr;
+    int* slot = nullptr;
+    double total_ms[K_COUNT] = {};
+    long launches[K_COUNT] = {};
+};
+Profiler g_prof;
+
+struct ProfScope {
+    int idx;
+    hipStream_t s;
+    ProfScope(int slot, hipStream_t st) : idx(-1), s(st) {
+        if (g_prof.on && g_prof.used < g_prof.cap) {
+            idx = g_prof.used++;
+            g_prof.slot[idx] = slot;
+            (void)hipEventRecord(g_prof.beg[idx], s);
+        }
+    }
+    ~ProfScope() {
+        if (idx >= 0) (void)hipEventRecord(g_prof.end[idx], s);
+    }
+};
+#define TFLA_LAUNCH(slot, expr)     \
+    do {                            \
+        ProfScope ps_((slot), s);   \
+        TFLA_TRY(expr);             \
+    } while (0)
+
+void prof_collect() {
+    for (int i = 0; i < g_prof.used; ++i) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(g_prof.end[i]) == hipSuccess &&
+            hipEventElapsedTime(&ms, g_prof.beg[i], g_prof.end[i]) == hipSuccess) {
+            g_prof.total_ms[g_prof.slot[i]] += ms;
+            g_prof.launches[g_prof.slot[i]] += 1;
+        }
+    }
+    g_prof.used = 0;
+}
+
 int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float* m0, float* wrow, float* ucol,
               float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, hipStream_t s) {
     GateArgs g;
@@ -111,7 +159,7 @@ int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float
     g.T = d.T; g.L = d.L; g.Nc = d.Nc; g.variant = d.variant;
     g.qscale = 1.0f / sqrtf((float)d.dqk);
     g.wrow = wrow; g.ucol = ucol; g.sH = sH; g.aK = aK; g.gbar = gbar; g.mout = mout; g.mfinal = mfinal; g.tmp = tmp;
-    TFLA_TRY(launch_gates(g, (int)d.BH, s));
+    TFLA_LAUNCH(K_GATES, launch_gates(g, (int)d.BH, s));
     return TFLA_OK;
 }
 
@@ -120,6 +168,41 @@ int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float
 extern "C" {
 
 int tfla_version(void) { return 1000; }
+
+int tfla_profile_enable(int max_launches) {
+    if (g_prof.beg) {
+        for (int i = 0; i < g_prof.cap; ++i) { (void)hipEventDestroy(g_prof.beg[i]); (void)hipEventDestroy(g_prof.end[i]); }
+        delete[] g_prof.beg; delete[] g_prof.end; delete[] g_prof.slot;
+        g_prof.beg = g_prof.end = nullptr; g_prof.slot = nullptr;
+    }
+    g_prof.on = false; g_prof.cap = 0; g_prof.used = 0;
+    for (int k = 0; k < K_COUNT; ++k) { g_prof.total_ms[k] = 0.0; g_prof.launches[k] = 0; }
+    if (max_launches <= 0) return TFLA_OK;
+    g_prof.beg = new hipEvent_t[max_launches]; g_prof.end = new hipEvent_t[max_launches];
+    g_prof.slot = new int[max_launches];
+    for (int i = 0; i < max_launches; ++i) {
+        hipError_t e = hipEventCreate(&g_prof.beg[i]);
+        if (e == hipSuccess) e = hipEventCreate(&g_prof.end[i]);
+        if (e != hipSuccess) return (int)e;
+    }
+    g_prof.cap = max_launches; g_prof.on = true;
+    return TFLA_OK;
+}
+
+int tfla_profile_read(int kernel, char* name, int name_len, double* total_ms, long* launches) {
+    if (kernel < 0 || kernel >= K_COUNT) return TFLA_ERR_ENUM;
+    prof_collect();
+    if (name && name_len > 0) {
+        int i = 0;
+        for (; i < name_len - 1 && kKernelNames[kernel][i]; ++i) name[i] = kKernelNames[kernel][i];
+        name[i] = 0;
+    }
+    if (total_ms) *total_ms = g_prof.total_ms[kernel];
+    if (launches) *launches = g_prof.launches[kernel];
+    return TFLA_OK;
+}
+
+int tfla_profile_kernels(void) { return K_COUNT; }
 
 const char* tfla_status_string(int status) {
     switch (status) {
@@ -176,7 +259,7 @@ int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_p
     r.stT = w.stT; r.stN = nullptr; r.Sfinal = Cn;
     r.n0 = is_exp ? n0 : nullptr; r.nst = is_exp ? w.nst : nullptr; r.nfinal = is_exp ? nn : nullptr;
     r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
-    TFLA_TRY(launch_recurrent(r, (int)d.BH, dtype, s));
+    TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
 
     // 3. parallel kernel
     TileArgs t;
@@ -185,13 +268,13 @@ int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_p
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
     t.variant = variant; t.eps = eps; t.nstate = w.nst; t.mout = mout; t.nout = is_exp ? n_out : nullptr;
     t.dotwith = nullptr; t.dotpart = nullptr;
-    TFLA_TRY(launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
+    TFLA_LAUNCH(K_TILE_H, launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
 
     if (!is_exp) {
-        if (nn) TFLA_TRY(launch_fill_zero(nn, d.BH * dqk, s));
-        if (mn) TFLA_TRY(launch_fill_zero(mn, d.BH, s));
-        if (n_out) TFLA_TRY(launch_fill_zero(n_out, d.BHT, s));
-        if (m_out) TFLA_TRY(launch_fill_zero(m_out, d.BHT, s));
+        if (nn) TFLA_LAUNCH(K_FILL, launch_fill_zero(nn, d.BH * dqk, s));
+        if (mn) TFLA_LAUNCH(K_FILL, launch_fill_zero(mn, d.BH, s));
+        if (n_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(n_out, d.BHT, s));
+        if (m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(m_out, d.BHT, s));
     }
     return TFLA_OK;
 }
@@ -222,7 +305,7 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     GateBwdPrepArgs p;
     p.wrow = w.wrow; p.sH = w.sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
     p.n = d.BHT; p.variant = variant; p.eps = eps;
-    TFLA_TRY(launch_gate_bwd_prep(p, s));
+    TFLA_LAUNCH(K_BWD_PREP, launch_gate_bwd_prep(p, s));
 
     // 2. recompute the chunk states C_{k-1} (layout d_qk x d_hv, read by the dQ kernel)
     RecArgs r;
@@ -230,7 +313,7 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     r.stT = nullptr; r.stN = w.cN; r.Sfinal = dCn ? w.Cfinal : nullptr;
     r.n0 = nullptr; r.nst = nullptr; r.nfinal = nullptr;
     r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
-    TFLA_TRY(launch_recurrent(r, (int)d.BH, dtype, s));
+    TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
 
     // 3. backward recurrence: dC_k for every chunk (both layouts), dC_0 at the end
     RecArgs rb;
@@ -238,7 +321,7 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     rb.stT = w.dcT; rb.stN = w.dcN; rb.Sfinal = dC0;
     rb.n0 = nullptr; rb.nst = nullptr; rb.nfinal = nullptr;
     rb.T = T; rb.L = chunk; rb.Nc = d.Nc; rb.d1 = dqk; rb.d2 = dhv; rb.reverse = 1;
-    TFLA_TRY(launch_recurrent(rb, (int)d.BH, dtype, s));
+    TFLA_LAUNCH(K_REC_BWD, launch_recurrent(rb, (int)d.BH, dtype, s));
 
     // 4. the three gradient kernels
     TileArgs t;
@@ -247,23 +330,23 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     // dV: rows = kv index j
     t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = w.ucol; t.wcol = w.wrowB; t.srow = w.aK; t.St = w.dcT;
     t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
-    TFLA_TRY(launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
+    TFLA_LAUNCH(K_TILE_DV, launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
     // dQ: rows = query index i
     t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = w.wrowB; t.wcol = w.ucol; t.srow = w.sQ; t.St = w.cN;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = q; t.dotpart = w.partQ;
-    TFLA_TRY(launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
+    TFLA_LAUNCH(K_TILE_DQ, launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
     // dK: rows = kv index j
     t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = w.ucol; t.wcol = w.wrowB; t.srow = w.aK; t.St = w.dcN;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = k; t.dotpart = w.partK;
-    TFLA_TRY(launch_tile_mode<MODE_DK>(t, (int)d.BH, dtype, s));
+    TFLA_LAUNCH(K_TILE_DK, launch_tile_mode<MODE_DK>(t, (int)d.BH, dtype, s));
 
     // 5. gate gradients
-    if (dCn) TFLA_TRY(launch_state_dot(w.Cfinal, dCn, w.cdot, (long)dqk * dhv, (int)d.BH, s));
+    if (dCn) TFLA_LAUNCH(K_STATE_DOT, launch_state_dot(w.Cfinal, dCn, w.cdot, (long)dqk * dhv, (int)d.BH, s));
     GateGradArgs gg;
     gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
     gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
     gg.BHT = d.BHT;
-    TFLA_TRY(launch_gate_grads(gg, (int)d.BH, s));
+    TFLA_LAUNCH(K_GATE_GRADS, launch_gate_grads(gg, (int)d.BH, s));
     return TFLA_OK;
 }
 

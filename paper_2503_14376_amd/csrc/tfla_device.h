@@ -164,6 +164,190 @@ __device__ __forceinline__ void stage_transposed(float* lds, int lstride, const 
 }
 
 // ---------------------------------------------------------------------------------------
+// Split (prefetching) forms of the two stagers: load() issues the global loads into
+// registers, store() writes them to LDS later, so the loads of the next tile are in flight
+// while the current tile is being multiplied.
+// ---------------------------------------------------------------------------------------
+template <typename DT, int ROWS, int COLS, int NT> struct RowsPrefetch {
+    static constexpr int EPC = 16 / (int)sizeof(DT), CPR = COLS / EPC, TOTAL = ROWS * CPR;
+    static constexpr int N = (TOTAL + NT - 1) / NT;
+    u32x4 r[N];
+    __device__ __forceinline__ void load(const DT* g, long gstride, int tid) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = tid + i * NT;
+            if (TOTAL % NT == 0 || c < TOTAL)
+                r[i] = *reinterpret_cast<const u32x4*>(g + (long)(c / CPR) * gstride + (c % CPR) * EPC);
+        }
+    }
+    __device__ __forceinline__ void store(DT* lds, int lstride, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = tid + i * NT;
+            if (TOTAL % NT == 0 || c < TOTAL)
+                *reinterpret_cast<u32x4*>(lds + (c / CPR) * lstride + (c % CPR) * EPC) = r[i];
+        }
+    }
+};
+
+template <typename DT, int ROWS, int COLS, int NT, bool PERM> struct TrPrefetch;
+
+template <int ROWS, int COLS, int NT, bool PERM> struct TrPrefetch<bf16_t, ROWS, COLS, NT, PERM> {
+    static constexpr int UNITS = (ROWS / 8) * (COLS / 2), N = (UNITS + NT - 1) / NT;
+    uint32_t w[N][8];
+    __device__ __forceinline__ void load(const bf16_t* g, long gstride, int tid) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int idx = tid + i * NT;
+            if (UNITS % NT == 0 || idx < UNITS) {
+                const int cp = idx % (COLS / 2), u = idx / (COLS / 2);
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    w[i][e] = *reinterpret_cast<const uint32_t*>(g + (long)tr_src_row<PERM>(u, e) * gstride + 2 * cp);
+            }
+        }
+    }
+    // per-unit row scales held in registers (rs[i][e] = scale of source row 8u+e; PERM = false)
+    __device__ __forceinline__ void load_scales(float (&rs)[N][8], const float* g, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int idx = tid + i * NT;
+            if (UNITS % NT == 0 || idx < UNITS) {
+                const int u = idx / (COLS / 2);
+                const f32x4 a = *reinterpret_cast<const f32x4*>(g + 8 * u), b = *reinterpret_cast<const f32x4*>(g + 8 * u + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { rs[i][e] = a[e]; rs[i][4 + e] = b[e]; }
+            }
+        }
+    }
+    __device__ __forceinline__ void store_scaled(bf16_t* lds, int lstride, const float (&rs)[N][8], int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int idx = tid + i * NT;
+            if (UNITS % NT == 0 || idx < UNITS) {
+                const int cp = idx % (COLS / 2), u = idx / (COLS / 2);
+                uint32_t x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    x[e] = bf16_bits_rne(bf16_lo_to_f32(w[i][e]) * rs[i][e]) | (bf16_bits_rne(bf16_hi_to_f32(w[i][e]) * rs[i][e]) << 16);
+                u32x4 lo, hi;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    lo[d] = (x[2 * d] & 0xffffu) | (x[2 * d + 1] << 16);
+                    hi[d] = (x[2 * d] >> 16) | (x[2 * d + 1] & 0xffff0000u);
+                }
+                *reinterpret_cast<u32x4*>(lds + (2 * cp) * lstride + 8 * u) = lo;
+                *reinterpret_cast<u32x4*>(lds + (2 * cp + 1) * lstride + 8 * u) = hi;
+            }
+        }
+    }
+    // rowscale (LDS or global, indexed by source row) may be null
+    template <bool SCALE>
+    __device__ __forceinline__ void store(bf16_t* lds, int lstride, const float* rowscale, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int idx = tid + i * NT;
+            if (UNITS % NT == 0 || idx < UNITS) {
+                const int cp = idx % (COLS / 2), u = idx / (COLS / 2);
+                uint32_t x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    x[e] = w[i][e];
+                    if (SCALE) {
+                        const float s = rowscale[tr_src_row<PERM>(u, e)];
+                        x[e] = bf16_bits_rne(bf16_lo_to_f32(x[e]) * s) | (bf16_bits_rne(bf16_hi_to_f32(x[e]) * s) << 16);
+                    }
+                }
+                u32x4 lo, hi;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    lo[d] = (x[2 * d] & 0xffffu) | (x[2 * d + 1] << 16);
+                    hi[d] = (x[2 * d] >> 16) | (x[2 * d + 1] & 0xffff0000u);
+                }
+                *reinterpret_cast<u32x4*>(lds + (2 * cp) * lstride + 8 * u) = lo;
+                *reinterpret_cast<u32x4*>(lds + (2 * cp + 1) * lstride + 8 * u) = hi;
+            }
+        }
+    }
+};
+
+template <int ROWS, int COLS, int NT, bool PERM> struct TrPrefetch<float, ROWS, COLS, NT, PERM> {
+    static constexpr int UNITS = (ROWS / 8) * COLS, N = (UNITS + NT - 1) / NT;
+    float w[N][8];
+    __device__ __forceinline__ void load(const float* g, long gstride, int tid) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int idx = tid + i * NT;
+            if (UNITS % NT == 0 || idx < UNITS) {
+                const int col = idx % COLS, u = idx / COLS;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[i][e] = g[(long)tr_src_row<PERM>(u, e) * gstride + col];
+            }
+        }
+    }
+    __device__ __forceinline__ void load_scales(float (&rs)[N][8], const float* g, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int idx = tid + i * NT;
+            if (UNITS % NT == 0 || idx < UNITS) {
+                const int u = idx / COLS;
+                const f32x4 a = *reinterpret_cast<const f32x4*>(g + 8 * u), b = *reinterpret_cast<const f32x4*>(g + 8 * u + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { rs[i][e] = a[e]; rs[i][4 + e] = b[e]; }
+            }
+        }
+    }
+    __device__ __forceinline__ void store_scaled(float* lds, int lstride, const float (&rs)[N][8], int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int idx = tid + i * NT;
+            if (UNITS % NT == 0 || idx < UNITS) {
+                const int col = idx % COLS, u = idx / COLS;
+                f32x4 a = {w[i][0] * rs[i][0], w[i][1] * rs[i][1], w[i][2] * rs[i][2], w[i][3] * rs[i][3]};
+                f32x4 b = {w[i][4] * rs[i][4], w[i][5] * rs[i][5], w[i][6] * rs[i][6], w[i][7] * rs[i][7]};
+                *reinterpret_cast<f32x4*>(lds + col * lstride + 8 * u) = a;
+                *reinterpret_cast<f32x4*>(lds + col * lstride + 8 * u + 4) = b;
+            }
+        }
+    }
+    template <bool SCALE>
+    __device__ __forceinline__ void store(float* lds, int lstride, const float* rowscale, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int idx = tid + i * NT;
+            if (UNITS % NT == 0 || idx < UNITS) {
+                const int col = idx % COLS, u = idx / COLS;
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = SCALE ? w[i][e] * rowscale[tr_src_row<PERM>(u, e)] : w[i][e];
+                f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
+                *reinterpret_cast<f32x4*>(lds + col * lstride + 8 * u) = a;
+                *reinterpret_cast<f32x4*>(lds + col * lstride + 8 * u + 4) = b;
+            }
+        }
+    }
+};
+
+// four consecutive elements as one store (8 bytes of bf16, 16 bytes of fp32)
+__device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, float d) {
+    uint2 w;
+    w.x = bf16_bits_rne(a) | (bf16_bits_rne(b) << 16);
+    w.y = bf16_bits_rne(c) | (bf16_bits_rne(d) << 16);
+    *reinterpret_cast<uint2*>(p) = w;
+}
+__device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
+    f32x4 w = {a, b, c, d};
+    *reinterpret_cast<f32x4*>(p) = w;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by their linear id.  This remaps the
+// hardware id so that each XCD (and its L2) works on a contiguous range of logical ids.
+__device__ __forceinline__ unsigned xcd_remap(unsigned hw, unsigned total) {
+    if (total % 8u != 0u) return hw;
+    return (hw % 8u) * (total / 8u) + hw / 8u;
+}
+
+// ---------------------------------------------------------------------------------------
 // Wavefront helpers (64 lanes)
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float x) {

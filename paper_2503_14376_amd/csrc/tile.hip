@@ -22,34 +22,48 @@
 // already laid out as the A operand of the second product.
 #include "tfla_device.h"
 #include "tfla_internal.h"
+#include "tile_fast.h"
 
 namespace tfla {
 
+// Generic kernel (any element type; operands staged through registers).  bf16 uses
+// tile_kernel_bf16 (tile_fast.h); this one serves fp32.
 template <typename DT, int D1, int BD2, int BC, int NW, int MODE>
 __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     using E = Elem<DT>;
     using frag = typename E::frag;
     constexpr bool UPPER = (MODE & 1) != 0;
     constexpr int NT = NW * 64, BR = NW * 32;
-    constexpr int KS1 = D1 / 16, NB = BD2 / 32;
+    constexpr int KS1 = D1 / 16, NB = BD2 / 32, NK = D1 / BC;
     constexpr int YS = D1 + E::PAD, ZS = BC + E::PAD;
-    __shared__ __attribute__((aligned(16))) DT ldsY[BC * YS];
-    __shared__ __attribute__((aligned(16))) DT ldsZ[BD2 * ZS];
-    __shared__ float ldsW[BC];
+    // two stages of (Y tile, Z tile, column weights): one is multiplied while the other is filled
+    __shared__ __attribute__((aligned(16))) DT ldsY[2][BC * YS];
+    __shared__ __attribute__((aligned(16))) DT ldsZ[2][BD2 * ZS];
+    __shared__ float ldsW[2][BC];
     __shared__ float ldsR[NW * 32];
     __shared__ float ldsN[(MODE == MODE_H) ? D1 : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
-    const int nb2 = blockIdx.x, rb = blockIdx.y;
-    const int kc = blockIdx.z % a.Nc, bh = blockIdx.z / a.Nc;
+    // XCD-aware decomposition of the workgroup id: the workgroups of one chunk (all d2 blocks
+    // and row blocks, which share K/V/state tiles) are neighbours on one XCD.
+    const unsigned nwg = gridDim.x * gridDim.y * gridDim.z;
+    unsigned wg = xcd_remap(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), nwg);
+    const int nb2 = wg % gridDim.x; wg /= gridDim.x;
+    // later row blocks of a lower-triangular kernel (earlier ones of an upper one) have more
+    // column tiles: start them first
+    const int rbi = wg % gridDim.y; wg /= gridDim.y;
+    const int rb = UPPER ? rbi : (int)gridDim.y - 1 - rbi;
+    const int kc = wg % a.Nc, bh = wg / a.Nc;
     const long tbase = (long)bh * a.T + (long)kc * a.L;   // first step of the chunk
     const int r0 = rb * BR;                               // chunk-local first row of the workgroup
     const int wr0 = r0 + wave * 32;                       // ... of the wavefront
     const int d2 = a.d2;
 
     const DT* X = reinterpret_cast<const DT*>(a.X);
-    const DT* Y = reinterpret_cast<const DT*>(a.Y);
-    const DT* Z = reinterpret_cast<const DT*>(a.Z);
+    const DT* Y = reinterpret_cast<const DT*>(a.Y) + tbase * D1;
+    const DT* Z = reinterpret_cast<const DT*>(a.Z) + tbase * d2 + (long)nb2 * BD2;
+    const DT* St = reinterpret_cast<const DT*>(a.St) + (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * D1;
+    const float* wcol = a.wcol + tbase;
 
     // X fragments of the wavefront's 32 rows (lane: row l32, k-group g)
     frag xf[KS1];
@@ -58,6 +72,10 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks) xf[ks] = E::load(xr + 16 * ks);
     }
+    if (MODE == MODE_H) {
+        if (a.variant == 0)
+            for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * D1 + i];
+    }
 
     f32x16 acc[NB];
 #pragma unroll
@@ -65,23 +83,45 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
 
-    // ---------------- inter-chunk part: acc = X_r St, BC columns of d1 at a time
-    {
-        const DT* St = reinterpret_cast<const DT*>(a.St) + (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * D1;
+    const int ct_lo = UPPER ? r0 / BC : 0;
+    const int ct_hi = UPPER ? a.L / BC : (r0 + BR) / BC;
+
+    RowsPrefetch<DT, BD2, BC, NT> ps;          // state chunk  [BD2][BC]
+    RowsPrefetch<DT, BC, D1, NT> py;           // Y tile       [BC][D1]
+    TrPrefetch<DT, BC, BD2, NT, true> pz;      // Z tile       [BC][BD2] -> [BD2][BC]
+    float pw = 0.0f;
+    int buf = 0;
+
+    // ---------------- inter-chunk part: acc = X_r St, BC columns of d1 per stage
+    ps.load(St, D1, tid);
+    ps.store(ldsZ[0], ZS, tid);
+    __syncthreads();
 #pragma unroll
-        for (int kk = 0; kk < D1; kk += BC) {
-            __syncthreads();
-            stage_rows<DT, BD2, BC, NT>(ldsZ, ZS, St + kk, D1, tid);
-            __syncthreads();
-#pragma unroll
-            for (int ks = 0; ks < BC / 16; ++ks) {
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const frag b = E::load(ldsZ + (nb * 32 + l32) * ZS + 16 * ks + 8 * g);
-                    acc[nb] = E::mma(xf[kk / 16 + ks], b, acc[nb]);
-                }
-            }
+    for (int j = 0; j < NK; ++j) {
+        if (j + 1 < NK) {
+            ps.load(St + (j + 1) * BC, D1, tid);
+        } else {
+            py.load(Y + (long)ct_lo * BC * D1, D1, tid);
+            pz.load(Z + (long)ct_lo * BC * d2, d2, tid);
+            if (tid < BC) pw = wcol[ct_lo * BC + tid];
         }
+        const DT* zb = ldsZ[buf];
+#pragma unroll
+        for (int ks = 0; ks < BC / 16; ++ks)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb] = E::mma(xf[j * (BC / 16) + ks], E::load(zb + (nb * 32 + l32) * ZS + 16 * ks + 8 * g), acc[nb]);
+        if (j + 1 < NK) {
+            ps.store(ldsZ[buf ^ 1], ZS, tid);
+        } else {
+            py.store(ldsY[buf ^ 1], YS, tid);
+            pz.template store<false>(ldsZ[buf ^ 1], ZS, nullptr, tid);
+            if (tid < BC) ldsW[buf ^ 1][tid] = pw;
+        }
+        __syncthreads();
+        buf ^= 1;
+    }
+    {
         float sr[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) sr[v] = a.srow[tbase + wr0 + acc_row(v, g)];
@@ -95,9 +135,6 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     float nrm = 0.0f;
     if (MODE == MODE_H) {
         if (a.variant == 0) {
-            __syncthreads();
-            for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * D1 + i];
-            __syncthreads();
             float dot = 0.0f;
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks)
@@ -111,15 +148,17 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     // ---------------- intra-chunk part
     const float wr = a.wrow[tbase + wr0 + l32];
     float rowsum = 0.0f;
-    const int ct_lo = UPPER ? r0 / BC : 0;
-    const int ct_hi = UPPER ? a.L / BC : (r0 + BR) / BC;
     for (int ct = ct_lo; ct < ct_hi; ++ct) {
         const int c0 = ct * BC;
-        __syncthreads();
-        stage_rows<DT, BC, D1, NT>(ldsY, YS, Y + (tbase + c0) * D1, D1, tid);
-        stage_transposed<BC, BD2, NT, true, false>(ldsZ, ZS, Z + (tbase + c0) * d2 + (long)nb2 * BD2, d2, nullptr, tid);
-        if (tid < BC) ldsW[tid] = a.wcol[tbase + c0 + tid];
-        __syncthreads();
+        const bool more = ct + 1 < ct_hi;
+        if (more) {
+            py.load(Y + (long)(c0 + BC) * D1, D1, tid);
+            pz.load(Z + (long)(c0 + BC) * d2, d2, tid);
+            if (tid < BC) pw = wcol[c0 + BC + tid];
+        }
+        const DT* yb = ldsY[buf];
+        const DT* zb = ldsZ[buf];
+        const float* wb = ldsW[buf];
 #pragma unroll
         for (int st = 0; st < BC / 32; ++st) {
             const int cs = c0 + 32 * st;
@@ -129,15 +168,13 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) s[v] = 0.0f;
 #pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) {
-                const frag ya = E::load(ldsY + (32 * st + l32) * YS + 16 * ks + 8 * g);
-                s = E::mma(ya, xf[ks], s);
-            }
+            for (int ks = 0; ks < KS1; ++ks)
+                s = E::mma(E::load(yb + (32 * st + l32) * YS + 16 * ks + 8 * g), xf[ks], s);
             float p[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int cl = acc_row(v, g);
-                float w = fast_exp2(wr + ldsW[32 * st + cl]);
+                float w = fast_exp2(wr + wb[32 * st + cl]);
                 if (diag) {
                     const bool keep = UPPER ? (cs + cl >= wr0 + l32) : (cs + cl <= wr0 + l32);
                     w = keep ? w : 0.0f;
@@ -148,11 +185,18 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
             const frag p0 = E::pack(p), p1 = E::pack(p + 8);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                const DT* zrow = ldsZ + (nb * 32 + l32) * ZS + 32 * st + 8 * g;
+                const DT* zrow = zb + (nb * 32 + l32) * ZS + 32 * st + 8 * g;
                 acc[nb] = E::mma(p0, E::load(zrow), acc[nb]);
                 acc[nb] = E::mma(p1, E::load(zrow + 16), acc[nb]);
             }
         }
+        if (more) {
+            py.store(ldsY[buf ^ 1], YS, tid);
+            pz.template store<false>(ldsZ[buf ^ 1], ZS, nullptr, tid);
+            if (tid < BC) ldsW[buf ^ 1][tid] = pw;
+        }
+        __syncthreads();
+        buf ^= 1;
     }
 
     // ---------------- epilogue
@@ -200,9 +244,13 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 // ------------------------------------------------------------------------------------------
 template <typename DT, int D1, int BD2, int NW, int MODE>
 static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
-    constexpr int BC = sizeof(DT) == 2 ? 64 : 32;
     dim3 grid(a.d2 / BD2, a.L / (32 * NW), BH * a.Nc);
-    hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE>), grid, dim3(64 * NW), 0, s, a);
+    if constexpr (sizeof(DT) == 2) {
+        hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE>), grid, dim3(64 * NW), 0, s, a);
+    } else {
+        constexpr int BC = 32;   // two LDS stages must fit in 160 KB
+        hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE>), grid, dim3(64 * NW), 0, s, a);
+    }
     return hipGetLastError();
 }
 

@@ -1,0 +1,286 @@
+// bf16 fast path of the intra-chunk tiled kernels (see tile.hip for what is computed).
+//
+// Every operand tile reaches LDS through asynchronous global->LDS loads in a ring of NS
+// stages; nothing is staged through registers and no VALU work is spent on data movement.
+// Column tiles are BC = 32 wide.  Per stage: Y tile [32][D1] (k-contiguous fragments) and
+// Z tile [32][BD2] (read through the transposing LDS read, because its contraction index is
+// the row index); the inter-chunk state is streamed through the same ring in [BD2][BCS]
+// slices before the column tiles.
+#pragma once
+#include "lds_tiles.h"
+#include "tfla_internal.h"
+
+namespace tfla {
+
+template <int D1, int BD2, int NW, int MODE>
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1))) tile_kernel_bf16(TileArgs a) {
+    using E = Elem<bf16_t>;
+    using frag = E::frag;
+    constexpr bool UPPER = (MODE & 1) != 0;
+    constexpr int NT = NW * 64, BR = NW * 32, BC = 32;
+    constexpr int KS1 = D1 / 16, NB = BD2 / 32;
+    constexpr int YB = BC * D1 * 2, ZB = BC * BD2 * 2, STAGE = YB + ZB;             // bytes
+    constexpr int NS = STAGE * 4 <= 131072 ? 4 : (STAGE * 3 <= 147456 ? 3 : 2);
+    constexpr int BCS_RAW = STAGE / (BD2 * 2);
+    constexpr int BCS = BCS_RAW >= D1 ? D1 : (BCS_RAW >= 64 ? 64 : 32);             // state slice width
+    constexpr int NKS = D1 / BCS;
+    static_assert(BD2 * BCS * 2 <= STAGE && BCS <= 64 && D1 % BCS == 0, "state slice must fit a stage");
+    constexpr int MAXL = 2048;
+
+    __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
+    __shared__ float ldsW[MAXL];
+    __shared__ float ldsR[NW * 32];
+    __shared__ float ldsN[(MODE == MODE_H) ? D1 : 1];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const unsigned nwg = gridDim.x * gridDim.y * gridDim.z;
+    unsigned wg = xcd_remap(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), nwg);
+    const int nb2 = wg % gridDim.x; wg /= gridDim.x;
+    const int rbi = wg % gridDim.y; wg /= gridDim.y;
+    const int rb = UPPER ? rbi : (int)gridDim.y - 1 - rbi;      // row blocks with more column tiles first
+    const int kc = wg % a.Nc, bh = wg / a.Nc;
+    const long tbase = (long)bh * a.T + (long)kc * a.L;
+    const int r0 = rb * BR, wr0 = r0 + wave * 32;
+    const int d2 = a.d2;
+
+    const bf16_t* X = reinterpret_cast<const bf16_t*>(a.X);
+    const bf16_t* Y = reinterpret_cast<const bf16_t*>(a.Y) + tbase * D1;
+    const bf16_t* Z = reinterpret_cast<const bf16_t*>(a.Z) + tbase * d2 + (long)nb2 * BD2;
+    const bf16_t* St = reinterpret_cast<const bf16_t*>(a.St) + (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * D1;
+
+    const int ct_lo = UPPER ? r0 / BC : 0;
+    const int ct_hi = UPPER ? a.L / BC : (r0 + BR) / BC;
+    const int NI = NKS + (ct_hi - ct_lo);                       // items streamed through the ring
+
+    DmaTile<BD2, BCS, NT, SWZ_K> ds;  ds.init(D1, tid);
+    DmaTile<BC, D1, NT, SWZ_K> dy;    dy.init(D1, tid);
+    DmaTile<BC, BD2, NT, SWZ_T> dz;   dz.init(d2, tid);
+    constexpr int CS = DmaTile<BD2, BCS, NT, SWZ_K>::N;
+    constexpr int CT = DmaTile<BC, D1, NT, SWZ_K>::N + DmaTile<BC, BD2, NT, SWZ_T>::N;
+    const uint32_t smem_a = lds_addr(smem);
+
+    auto issue = [&](int item) {
+        const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
+        if (item < NKS) {
+            ds.issue(St + item * BCS, st, tid);
+        } else {
+            const int ct = ct_lo + item - NKS;
+            dy.issue(Y + (long)ct * BC * D1, st, tid);
+            dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
+        }
+    };
+    // loads of this wave issued after those of item i and still allowed in flight while waiting for i
+    auto pending_after = [&](int i) {
+        int p = 0;
+#pragma unroll
+        for (int j = 1; j <= NS - 2; ++j)
+            if (i + j < NI) p += (i + j < NKS) ? CS : CT;
+        return p;
+    };
+
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < NI) issue(p);
+
+    // X fragments of the wavefront's 32 rows (lane: row l32, k-group g), straight from global
+    frag xf[KS1];
+    {
+        const bf16_t* xr = X + (tbase + wr0 + l32) * D1 + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks) xf[ks] = E::load(xr + 16 * ks);
+    }
+    for (int i = tid; i < a.L; i += NT) ldsW[i] = a.wcol[tbase + i];
+    if (MODE == MODE_H) {
+        if (a.variant == 0)
+            for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * D1 + i];
+    }
+    // make the plain loads above complete before the ring's wait counts are relied upon
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    KFragReader<BCS> rs_;  rs_.init(l32, g);
+    KFragReader<D1> ry;    ry.init(l32, g);
+    TFragReader<BD2> rz;   rz.init(lane, 4);
+
+    f32x16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+
+    // ---------------- inter-chunk part: acc = X_r St
+#pragma unroll
+    for (int i = 0; i < NKS; ++i) {
+        wait_vmcnt_dyn(pending_after(i));
+        barrier_nofence();
+        if (i + NS - 1 < NI) issue(i + NS - 1);
+        const char* sb = smem + (i % NS) * STAGE;
+        {
+            constexpr int NF = (BCS / 16) * NB;
+            frag b[BCS / 16][NB];
+#pragma unroll
+            for (int ks = 0; ks < BCS / 16; ++ks)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) b[ks][nb].v = rs_.load(sb, ks, nb);
+#pragma unroll
+            for (int ks = 0; ks < BCS / 16; ++ks)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(xf[i * (BCS / 16) + ks], b[ks][nb], acc[nb]);
+            constexpr int PF = NF < 4 ? NF : 4;
+#pragma unroll
+            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+            for (int q = 0; q < NF - PF; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+    }
+    {
+        float sr[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sr[v] = a.srow[tbase + wr0 + acc_row(v, g)];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][v] *= sr[v];
+    }
+    float nrm = 0.0f;
+    if (MODE == MODE_H) {
+        if (a.variant == 0) {
+            float dot = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot += E::frag_elem(xf[ks], e) * ldsN[16 * ks + 8 * g + e];
+            dot += __shfl_xor(dot, 32, 64);
+            nrm = dot * a.srow[tbase + wr0 + l32];
+        }
+    }
+    const float wr = a.wrow[tbase + wr0 + l32];
+    // Force the compiler's own wait for these plain loads to sit here, outside the tile loop: a
+    // wait placed at their first use inside the loop would also drain the ring on every pass.
+    asm volatile("" ::"v"(wr), "v"(nrm));
+
+    // ---------------- intra-chunk part, one 32-column tile per item
+    float rowsum = 0.0f;
+    for (int ct = ct_lo; ct < ct_hi; ++ct) {
+        const int i = NKS + ct - ct_lo;
+        wait_vmcnt_dyn(pending_after(i));
+        barrier_nofence();
+        if (i + NS - 1 < NI) issue(i + NS - 1);
+        const int cs = ct * BC;
+        if (UPPER ? (cs + 31 < wr0) : (cs > wr0 + 31)) continue;      // fully masked for this wave
+        const bool diag = UPPER ? (cs < wr0 + 31) : (cs + 31 > wr0);
+        const char* yb = smem + (i % NS) * STAGE;
+        const char* zb = yb + YB;
+        f32x16 s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.0f;
+        {
+            frag ya[KS1];
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) ya[ks].v = ry.load(yb, ks, 0);
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) s = E::mma(ya[ks], xf[ks], s);
+            // LDS reads run PF fragments ahead of the MFMAs that consume them
+            constexpr int PF = KS1 < 4 ? KS1 : 4;
+#pragma unroll
+            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+            for (int q = 0; q < KS1 - PF; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        float p[16];
+        if (diag) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int cl = acc_row(v, g);
+                const float w = fast_exp2(wr + ldsW[cs + cl]);
+                const bool keep = UPPER ? (cs + cl >= wr0 + l32) : (cs + cl <= wr0 + l32);
+                p[v] = keep ? s[v] * w : 0.0f;
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) p[v] = s[v] * fast_exp2(wr + ldsW[cs + acc_row(v, g)]);
+        }
+        if (MODE == MODE_H) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) rowsum += p[v];
+        }
+        const frag p0 = E::pack(p), p1 = E::pack(p + 8);
+        {
+            frag z[NB][2];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                z[nb][0].v = rz.load(zb, nb, 0, 8);
+                z[nb][1].v = rz.load(zb, nb, 16, 24);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                acc[nb] = E::mma(p0, z[nb][0], acc[nb]);
+                acc[nb] = E::mma(p1, z[nb][1], acc[nb]);
+            }
+            // every Z fragment pair costs four transposing reads; keep two pairs ahead
+            constexpr int PF = NB < 2 ? NB : 2;
+#pragma unroll
+            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int q = 0; q < NB - PF; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
+    }
+
+    // ---------------- epilogue
+    float inv[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) inv[v] = 1.0f;
+    if (MODE == MODE_H) {
+        if (a.variant == 0) {
+            rowsum += __shfl_xor(rowsum, 32, 64);
+            nrm += rowsum;
+            const long t = tbase + wr0 + l32;
+            const float den = fmaxf(fabsf(nrm), expf(-a.mout[t])) + a.eps;
+            if (g == 0) {
+                ldsR[wave * 32 + l32] = 1.0f / den;
+                if (a.nout && nb2 == 0) a.nout[t] = nrm;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) inv[v] = ldsR[wave * 32 + acc_row(v, g)];
+        }
+    }
+    bf16_t* Out = reinterpret_cast<bf16_t*>(a.Out);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const long t = tbase + wr0 + acc_row(v, g);
+            Out[t * d2 + (long)nb2 * BD2 + nb * 32 + l32] = E::from_f32(acc[nb][v] * inv[v]);
+        }
+    if (MODE == MODE_DQ || MODE == MODE_DK) {
+        const bf16_t* W = reinterpret_cast<const bf16_t*>(a.dotwith);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const long t = tbase + wr0 + acc_row(v, g);
+            float d = 0.0f;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                d += acc[nb][v] * E::to_f32(W[t * d2 + (long)nb2 * BD2 + nb * 32 + l32]);
+            d = half_sum(d);
+            if (l32 == 0) a.dotpart[(long)nb2 * ((long)gridDim.z / a.Nc) * a.T + t] = d;
+        }
+    }
+}
+
+}  // namespace tfla
