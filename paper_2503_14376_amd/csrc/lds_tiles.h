@@ -44,8 +44,13 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 // it; the kernels order these loads themselves with wait_vmcnt + barrier.
 __device__ __forceinline__ void dma16(const void* gbase_uniform, uint32_t voff, uint32_t lds_uniform) {
     const uint32_t la = __builtin_amdgcn_readfirstlane(lds_uniform);
+    const uint64_t gb = (uint64_t)(uintptr_t)gbase_uniform;
+    // readfirstlane returns a signed int: go through uint32_t so the low half is not sign-extended
+    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
+    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
+    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(la), "v"(voff), "s"(gbase_uniform) : "memory", "m0");
+                 :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
 }
 
 // workgroup barrier without the fence a __syncthreads() carries (that fence would wait for

@@ -12,6 +12,18 @@
 
 namespace tfla {
 
+// Development aid, compiled only with -DTFLA_TIMELINE: wave 0 of every workgroup records the
+// shader clock at phase boundaries.
+#ifdef TFLA_TIMELINE
+static __device__ unsigned long long tfla_timeline[1 << 18];
+#define TFLA_TL(k)                                                                                         \
+    if (tid == 0)                                                                                          \
+    tfla_timeline[((blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) * 8 + (k)) & ((1 << 18) - 1)] = \
+        __builtin_amdgcn_s_memtime()
+#else
+#define TFLA_TL(k)
+#endif
+
 template <int D1, int BD2, int NW, int MODE>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1))) tile_kernel_bf16(TileArgs a) {
     using E = Elem<bf16_t>;
@@ -33,6 +45,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
     __shared__ float ldsN[(MODE == MODE_H) ? D1 : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    TFLA_TL(0);
     const unsigned nwg = gridDim.x * gridDim.y * gridDim.z;
     unsigned wg = xcd_remap(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), nwg);
     const int nb2 = wg % gridDim.x; wg /= gridDim.x;
@@ -97,6 +110,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
     // make the plain loads above complete before the ring's wait counts are relied upon
     wait_vmcnt<0>();
     __syncthreads();
+    TFLA_TL(1);
 
     KFragReader<BCS> rs_;  rs_.init(l32, g);
     KFragReader<D1> ry;    ry.init(l32, g);
@@ -138,6 +152,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
             for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
     }
+    TFLA_TL(2);
     {
         float sr[16];
 #pragma unroll
@@ -164,6 +179,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
     // wait placed at their first use inside the loop would also drain the ring on every pass.
     asm volatile("" ::"v"(wr), "v"(nrm));
 
+    TFLA_TL(3);
     // ---------------- intra-chunk part, one 32-column tile per item
     float rowsum = 0.0f;
     for (int ct = ct_lo; ct < ct_hi; ++ct) {
@@ -241,6 +257,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
         }
     }
 
+    TFLA_TL(4);
     // ---------------- epilogue
     float inv[16];
 #pragma unroll
@@ -281,6 +298,11 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
             if (l32 == 0) a.dotpart[(long)nb2 * ((long)gridDim.z / a.Nc) * a.T + t] = d;
         }
     }
+    TFLA_TL(5);
+#ifdef TFLA_TIMELINE
+    wait_vmcnt<0>();
+    TFLA_TL(6);
+#endif
 }
 
 }  // namespace tfla

@@ -4,3 +4,9 @@
 #error "compile with -DTFLA_TILE_MODE=<0..3>"
 #endif
 #include "tile.hip"
+
+#if defined(TFLA_TIMELINE) && TFLA_TILE_MODE == 0
+extern "C" __attribute__((visibility("default"))) int tfla_debug_timeline(unsigned long long* host, size_t n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(tfla::tfla_timeline), n * sizeof(unsigned long long));
+}
+#endif
