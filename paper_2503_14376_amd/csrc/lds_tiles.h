@@ -53,6 +53,17 @@ __device__ __forceinline__ void dma16(const void* gbase_uniform, uint32_t voff, 
                  :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
 }
 
+// Same for 64 x 4 bytes: lane l copies one dword to LDS address lds_uniform + 4 * l.
+__device__ __forceinline__ void dma4(const void* gbase_uniform, uint32_t voff, uint32_t lds_uniform) {
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_uniform);
+    const uint64_t gb = (uint64_t)(uintptr_t)gbase_uniform;
+    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
+    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
+    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
+}
+
 // workgroup barrier without the fence a __syncthreads() carries (that fence would wait for
 // every outstanding global->LDS load, i.e. drain the pipeline)
 __device__ __forceinline__ void barrier_nofence() { asm volatile("s_barrier" ::: "memory"); }
@@ -129,6 +140,23 @@ template <int COLS> struct TFragReader {
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
             off[j] = (uint32_t)(row * RB + (((4 * j) ^ f) + 2 * (m & 1) + ((i & 3) >> 1)) * 16 + (i & 1) * 8);
+    }
+    // byte offset of column block nb for this lane; for callers whose nb is not a compile-time value
+    // (indexing off[] with a run-time value would push the array out of registers)
+    __device__ __forceinline__ uint32_t block_offset(int nb) const {
+        uint32_t o = off[0];
+#pragma unroll
+        for (int j = 1; j < NJ; ++j) o = (nb % NJ == j) ? off[j] : o;
+        return o + (uint32_t)(nb / NJ) * 256u;
+    }
+    // the same fragment read from a precomputed block_offset()
+    static __device__ __forceinline__ bf16x8 load_at(const char* tile, uint32_t boff, int rowA, int rowB) {
+        const char* p = tile + boff;
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (__attribute__((address_space(3))) bf16x4*)(p + rowA * RB));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (__attribute__((address_space(3))) bf16x4*)(p + rowB * RB));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
     // rows rowA.. and rowB.. (multiples of 4, before the lane part) give elements 0..3 and 4..7
     __device__ __forceinline__ bf16x8 load(const char* tile, int nb, int rowA, int rowB) const {

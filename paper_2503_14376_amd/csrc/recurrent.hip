@@ -10,8 +10,12 @@
 // layouts the tiled kernels read: stT[k] = state^T (d2 x d1) and stN[k] = state (d1 x d2).
 #include "tfla_device.h"
 #include "tfla_internal.h"
+#include "recurrent_fast.h"
 
 namespace tfla {
+
+// Generic kernel (any element type, operands staged transposed through registers); bf16 uses
+// recurrent_kernel_bf16 (recurrent_fast.h), this one serves fp32.
 
 template <typename DT, int MI, int NI, int BK>
 __global__ void __launch_bounds__(256) recurrent_kernel(RecArgs a) {
@@ -192,13 +196,26 @@ static hipError_t launch_rec_t(const RecArgs& a, int BH, hipStream_t s) {
     return hipGetLastError();
 }
 
+template <int WM, int WN, int MI, int NI>
+static hipError_t launch_rec_bf16(const RecArgs& a, int BH, hipStream_t s) {
+    dim3 grid(a.d2 / (WN * 32 * NI), a.d1 / (WM * 32 * MI), BH);
+    hipLaunchKernelGGL((recurrent_kernel_bf16<WM, WN, MI, NI>), grid, dim3(WM * WN * 64), 0, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_recurrent(const RecArgs& a, int BH, int dtype, hipStream_t s) {
     // 128x128 state tiles when that still fills the chip, 64x64 tiles otherwise
     const bool big_ok = (a.d1 % 128 == 0) && (a.d2 % 128 == 0);
     const long wg_big = (long)BH * (a.d1 / 128) * (a.d2 / 128);
     const bool big = big_ok && wg_big >= 192;
-    if (dtype == 1) return big ? launch_rec_t<bf16_t, 2, 2>(a, BH, s) : launch_rec_t<bf16_t, 1, 1>(a, BH, s);
+    if (dtype == 1) return big ? launch_rec_bf16<2, 4, 2, 1>(a, BH, s) : launch_rec_bf16<2, 2, 1, 1>(a, BH, s);
     return big ? launch_rec_t<float, 2, 2>(a, BH, s) : launch_rec_t<float, 1, 1>(a, BH, s);
 }
 
 }  // namespace tfla
+
+#ifdef TFLA_TIMELINE
+extern "C" __attribute__((visibility("default"))) int tfla_debug_rec_timeline(unsigned long long* host, size_t n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(tfla::tfla_rec_timeline), n * sizeof(unsigned long long));
+}
+#endif

@@ -34,6 +34,13 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
 __device__ __forceinline__ float bf16_lo_to_f32(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
 __device__ __forceinline__ float bf16_hi_to_f32(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// two fp32 values -> one dword of two bf16 (round to nearest even), a single v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    bf16x2 v = {(bf16_t)lo, (bf16_t)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
 template <typename DT> struct Elem;
 
 template <> struct Elem<bf16_t> {

@@ -48,10 +48,11 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
     TFLA_TL(0);
     const unsigned nwg = gridDim.x * gridDim.y * gridDim.z;
     unsigned wg = xcd_remap(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), nwg);
-    const int nb2 = wg % gridDim.x; wg /= gridDim.x;
-    const int rbi = wg % gridDim.y; wg /= gridDim.y;
+    const int nb2 = __builtin_amdgcn_readfirstlane((int)(wg % gridDim.x)); wg /= gridDim.x;
+    const int rbi = __builtin_amdgcn_readfirstlane((int)(wg % gridDim.y)); wg /= gridDim.y;
     const int rb = UPPER ? rbi : (int)gridDim.y - 1 - rbi;      // row blocks with more column tiles first
-    const int kc = wg % a.Nc, bh = wg / a.Nc;
+    const int kc = __builtin_amdgcn_readfirstlane((int)(wg % a.Nc));
+    const int bh = __builtin_amdgcn_readfirstlane((int)(wg / a.Nc));
     const long tbase = (long)bh * a.T + (long)kc * a.L;
     const int r0 = rb * BR, wr0 = r0 + wave * 32;
     const int d2 = a.d2;
