@@ -87,7 +87,7 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
     w.gbar = c.take<float>(d.BH * d.Nc);
     w.wrowB = c.take<float>(d.BHT); w.sQ = c.take<float>(d.BHT);
-    w.nbQ = d.dqk / tile_bd2(d.L, d.dqk, d.dtype);
+    w.nbQ = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype);
     w.nbK = w.nbQ;
     w.partQ = c.take<float>((size_t)w.nbQ * d.BHT); w.partK = c.take<float>((size_t)w.nbK * d.BHT);
     w.cdot = c.take<float>(d.BH);

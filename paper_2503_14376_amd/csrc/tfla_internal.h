@@ -84,11 +84,12 @@ struct TileArgs {
     float* dotpart;                 // (d2/BD2, BH*T)
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
-// d2 block of a tiled kernel: as wide as the register budget allows (256 for bf16 with
-// 128-row workgroups)
-inline int tile_bd2(int L, int d2, int dtype) {
-    const bool wide = dtype == 1 && (L % 128 == 0);
-    if (wide && d2 % 256 == 0) return 256;
+// d2 block of a tiled kernel with contraction width d1.  bf16, d1 <= 256: 128 columns, which keeps
+// a wavefront within 256 registers so that two workgroups share a CU (one hides the other's
+// prologue, epilogue and barriers); bf16, d1 = 512: the X fragments alone take 128 registers, so one
+// workgroup per CU with a 256-wide block; fp32: what the generic kernel's register budget allows.
+inline int tile_bd2(int d1, int d2, int dtype) {
+    if (dtype == 1 && d1 > 256 && d2 % 256 == 0) return 256;
     if (d2 % 128 == 0) return 128;
     return 64;
 }

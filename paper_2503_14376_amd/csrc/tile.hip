@@ -246,7 +246,9 @@ template <typename DT, int D1, int BD2, int NW, int MODE>
 static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
     dim3 grid(a.d2 / BD2, a.L / (32 * NW), BH * a.Nc);
     if constexpr (sizeof(DT) == 2) {
-        hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE>), grid, dim3(64 * NW), 0, s, a);
+        // two workgroups per CU when the accumulator is narrow enough for 256 registers per lane
+        constexpr int OCC = (BD2 <= 128 && D1 <= 256) ? 2 : 1;
+        hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC>), grid, dim3(64 * NW), 0, s, a);
     } else {
         constexpr int BC = 32;   // two LDS stages must fit in 160 KB
         hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE>), grid, dim3(64 * NW), 0, s, a);
@@ -257,7 +259,9 @@ static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
 template <typename DT, int D1, int MODE>
 static hipError_t launch_tile_d1(const TileArgs& a, int BH, int bd2, hipStream_t s) {
     if (a.L % 128 == 0) {
-        if (sizeof(DT) == 2 && bd2 == 256) return launch_tile_t<DT, D1, (sizeof(DT) == 2 ? 256 : 128), 4, MODE>(a, BH, s);
+        if constexpr (sizeof(DT) == 2 && D1 > 256) {
+            if (bd2 == 256) return launch_tile_t<DT, D1, 256, 4, MODE>(a, BH, s);
+        }
         if (bd2 == 128) return launch_tile_t<DT, D1, 128, 4, MODE>(a, BH, s);
         return launch_tile_t<DT, D1, 64, 4, MODE>(a, BH, s);
     }
@@ -281,7 +285,7 @@ static hipError_t launch_tile_m(const TileArgs& a, int BH, int bd2, hipStream_t 
 
 template <int MODE>
 hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s) {
-    const int bd2 = tile_bd2(a.L, a.d2, dtype);
+    const int bd2 = tile_bd2(a.d1, a.d2, dtype);
     return dtype == 1 ? launch_tile_m<bf16_t, MODE>(a, BH, bd2, s) : launch_tile_m<float, MODE>(a, BH, bd2, s);
 }
 

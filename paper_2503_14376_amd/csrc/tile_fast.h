@@ -24,23 +24,25 @@ static __device__ unsigned long long tfla_timeline[1 << 18];
 #define TFLA_TL(k)
 #endif
 
-template <int D1, int BD2, int NW, int MODE>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1))) tile_kernel_bf16(TileArgs a) {
+template <int D1, int BD2, int NW, int MODE, int OCC>
+__global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     using E = Elem<bf16_t>;
     using frag = E::frag;
     constexpr bool UPPER = (MODE & 1) != 0;
     constexpr int NT = NW * 64, BR = NW * 32, BC = 32;
     constexpr int KS1 = D1 / 16, NB = BD2 / 32;
     constexpr int YB = BC * D1 * 2, ZB = BC * BD2 * 2, STAGE = YB + ZB;             // bytes
-    constexpr int NS = STAGE * 4 <= 131072 ? 4 : (STAGE * 3 <= 147456 ? 3 : 2);
+    // LDS budget of one workgroup: 160 KB shared by OCC resident workgroups, minus the small arrays
+    constexpr int BUDGET = (OCC >= 2 ? 80 : 160) * 1024 - 6144;
+    constexpr int NS = STAGE * 4 <= BUDGET ? 4 : (STAGE * 3 <= BUDGET ? 3 : 2);
+    static_assert(NS * STAGE <= BUDGET, "ring does not fit");
     constexpr int BCS_RAW = STAGE / (BD2 * 2);
     constexpr int BCS = BCS_RAW >= D1 ? D1 : (BCS_RAW >= 64 ? 64 : 32);             // state slice width
     constexpr int NKS = D1 / BCS;
     static_assert(BD2 * BCS * 2 <= STAGE && BCS <= 64 && D1 % BCS == 0, "state slice must fit a stage");
-    constexpr int MAXL = 2048;
 
     __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
-    __shared__ float ldsW[MAXL];
+    __shared__ __attribute__((aligned(256))) float ldsW[NS][NW][64];   // column weights of a tile, one copy per wave
     __shared__ float ldsR[NW * 32];
     __shared__ float ldsN[(MODE == MODE_H) ? D1 : 1];
 
@@ -70,8 +72,9 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
     DmaTile<BC, D1, NT, SWZ_K> dy;    dy.init(D1, tid);
     DmaTile<BC, BD2, NT, SWZ_T> dz;   dz.init(d2, tid);
     constexpr int CS = DmaTile<BD2, BCS, NT, SWZ_K>::N;
-    constexpr int CT = DmaTile<BC, D1, NT, SWZ_K>::N + DmaTile<BC, BD2, NT, SWZ_T>::N;
-    const uint32_t smem_a = lds_addr(smem);
+    constexpr int CT = DmaTile<BC, D1, NT, SWZ_K>::N + DmaTile<BC, BD2, NT, SWZ_T>::N + 1;
+    const uint32_t smem_a = lds_addr(smem), w_a = lds_addr(ldsW);
+    const float* wcol = a.wcol + tbase;
 
     auto issue = [&](int item) {
         const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
@@ -81,6 +84,8 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
             const int ct = ct_lo + item - NKS;
             dy.issue(Y + (long)ct * BC * D1, st, tid);
             dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
+            // the tile's 32 column weights (both half-waves fetch the same 32 floats)
+            dma4(wcol + ct * BC, (uint32_t)(lane & 31) * 4u, w_a + (uint32_t)(((item % NS) * NW + wave) * 256));
         }
     };
     // loads of this wave issued after those of item i and still allowed in flight while waiting for i
@@ -103,7 +108,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks) xf[ks] = E::load(xr + 16 * ks);
     }
-    for (int i = tid; i < a.L; i += NT) ldsW[i] = a.wcol[tbase + i];
     if (MODE == MODE_H) {
         if (a.variant == 0)
             for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * D1 + i];
@@ -193,6 +197,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
         const bool diag = UPPER ? (cs < wr0 + 31) : (cs + 31 > wr0);
         const char* yb = smem + (i % NS) * STAGE;
         const char* zb = yb + YB;
+        const float* wb = &ldsW[i % NS][wave][0];
         f32x16 s;
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.0f;
@@ -219,13 +224,13 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1,
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int cl = acc_row(v, g);
-                const float w = fast_exp2(wr + ldsW[cs + cl]);
+                const float w = fast_exp2(wr + wb[cl]);
                 const bool keep = UPPER ? (cs + cl >= wr0 + l32) : (cs + cl <= wr0 + l32);
                 p[v] = keep ? s[v] * w : 0.0f;
             }
         } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) p[v] = s[v] * fast_exp2(wr + ldsW[cs + acc_row(v, g)]);
+            for (int v = 0; v < 16; ++v) p[v] = s[v] * fast_exp2(wr + wb[acc_row(v, g)]);
         }
         if (MODE == MODE_H) {
 #pragma unroll
