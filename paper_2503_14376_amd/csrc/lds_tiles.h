@@ -49,7 +49,10 @@ __device__ __forceinline__ void dma16(const void* gbase_uniform, uint32_t voff, 
     const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
     const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
     const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+    // s_nop 4: the hardware needs 5 wait states between a write of an SGPR (the base address, M0) and
+    // a vector-memory instruction that reads it; the compiler's hazard recogniser cannot see inside
+    // the asm, so the distance is guaranteed here
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
 }
 
@@ -60,8 +63,26 @@ __device__ __forceinline__ void dma4(const void* gbase_uniform, uint32_t voff, u
     const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
     const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
     const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dword %1, %2"
                  :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
+}
+
+// 2-byte stores of the low / high half of w to (uniform base + per-lane byte offset): the address
+// needs no vector arithmetic
+__device__ __forceinline__ void store_bf16_lo(void* base_uniform, uint32_t voff, uint32_t w) {
+    const uint64_t gb = (uint64_t)(uintptr_t)base_uniform;
+    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
+    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
+    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
+    // s_nop 4: 5 wait states between the SGPR write of the base and this read (see dma16)
+    asm volatile("s_nop 4\n\tglobal_store_short %0, %1, %2" :: "v"(voff), "v"(w), "s"(gu) : "memory");
+}
+__device__ __forceinline__ void store_bf16_hi(void* base_uniform, uint32_t voff, uint32_t w) {
+    const uint64_t gb = (uint64_t)(uintptr_t)base_uniform;
+    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
+    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
+    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
+    asm volatile("s_nop 4\n\tglobal_store_short_d16_hi %0, %1, %2" :: "v"(voff), "v"(w), "s"(gu) : "memory");
 }
 
 // workgroup barrier without the fence a __syncthreads() carries (that fence would wait for

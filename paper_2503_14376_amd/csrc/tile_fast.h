@@ -44,6 +44,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
     __shared__ __attribute__((aligned(256))) float ldsW[NS][NW][64];   // column weights of a tile, one copy per wave
     __shared__ float ldsR[NW * 32];
+    __shared__ float ldsS[BR];                       // inter-chunk row scale of the workgroup's rows
+    __shared__ float ldsM[(MODE == MODE_H) ? BR : 1];  // their max state (mLSTMexp forward)
     __shared__ float ldsN[(MODE == MODE_H) ? D1 : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
@@ -97,23 +99,32 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         return p;
     };
 
-#pragma unroll
-    for (int p = 0; p < NS - 1; ++p)
-        if (p < NI) issue(p);
-
-    // X fragments of the wavefront's 32 rows (lane: row l32, k-group g), straight from global
+    // X fragments of the wavefront's 32 rows (lane: row l32, k-group g), straight from global, and
+    // the per-row scalars of the workgroup's rows; issued before the ring so they return first
     frag xf[KS1];
     {
         const bf16_t* xr = X + (tbase + wr0 + l32) * D1 + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks) xf[ks] = E::load(xr + 16 * ks);
     }
+    const float wr = a.wrow[tbase + wr0 + l32];
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < NI) issue(p);
+    // (after the ring's first loads are on their way: the LDS writes below wait for their data)
+    if (tid < BR) {
+        ldsS[tid] = a.srow[tbase + r0 + tid];
+        if (MODE == MODE_H) ldsM[tid] = (a.variant == 0) ? a.mout[tbase + r0 + tid] : 0.0f;
+    }
     if (MODE == MODE_H) {
         if (a.variant == 0)
             for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * D1 + i];
     }
-    // make the plain loads above complete before the ring's wait counts are relied upon
+    // make the plain loads above complete before the ring's wait counts are relied upon; the empty
+    // asm makes the compiler place its own wait for wr here rather than at its first use inside the
+    // tile loop, where it would drain the ring on every pass
     wait_vmcnt<0>();
+    asm volatile("" ::"v"(wr));
     __syncthreads();
     TFLA_TL(1);
 
@@ -161,7 +172,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     {
         float sr[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sr[v] = a.srow[tbase + wr0 + acc_row(v, g)];
+        for (int v = 0; v < 16; ++v) sr[v] = ldsS[wave * 32 + acc_row(v, g)];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -176,14 +187,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dot += E::frag_elem(xf[ks], e) * ldsN[16 * ks + 8 * g + e];
             dot += __shfl_xor(dot, 32, 64);
-            nrm = dot * a.srow[tbase + wr0 + l32];
+            nrm = dot * ldsS[wave * 32 + l32];
         }
     }
-    const float wr = a.wrow[tbase + wr0 + l32];
-    // Force the compiler's own wait for these plain loads to sit here, outside the tile loop: a
-    // wait placed at their first use inside the loop would also drain the ring on every pass.
-    asm volatile("" ::"v"(wr), "v"(nrm));
-
     TFLA_TL(3);
     // ---------------- intra-chunk part, one 32-column tile per item
     float rowsum = 0.0f;
@@ -273,7 +279,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             rowsum += __shfl_xor(rowsum, 32, 64);
             nrm += rowsum;
             const long t = tbase + wr0 + l32;
-            const float den = fmaxf(fabsf(nrm), expf(-a.mout[t])) + a.eps;
+            const float den = fmaxf(fabsf(nrm), expf(-ldsM[wave * 32 + l32])) + a.eps;
             if (g == 0) {
                 ldsR[wave * 32 + l32] = 1.0f / den;
                 if (a.nout && nb2 == 0) a.nout[t] = nrm;
@@ -283,14 +289,23 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             for (int v = 0; v < 16; ++v) inv[v] = ldsR[wave * 32 + acc_row(v, g)];
         }
     }
-    bf16_t* Out = reinterpret_cast<bf16_t*>(a.Out);
+    // Output rows: registers v, v+1 of a lane are consecutive rows of one column.  Row addresses
+    // are formed on the scalar unit (uniform base per row) plus one per-lane offset, and two rows
+    // share one packed conversion.
+    {
+        char* out0 = reinterpret_cast<char*>(a.Out) + ((tbase + wr0) * d2 + (long)nb2 * BD2) * 2;
+        const uint32_t voff = (uint32_t)((4 * g * d2 + l32) * 2);
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+        for (int v = 0; v < 16; v += 2) {
+            const int rr = 8 * (v >> 2) + (v & 3);     // row of register v for lane group 0
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const long t = tbase + wr0 + acc_row(v, g);
-            Out[t * d2 + (long)nb2 * BD2 + nb * 32 + l32] = E::from_f32(acc[nb][v] * inv[v]);
+            for (int nb = 0; nb < NB; ++nb) {
+                const uint32_t w = pack_bf16x2(acc[nb][v] * inv[v], acc[nb][v + 1] * inv[v + 1]);
+                store_bf16_lo(out0 + ((long)rr * d2 + nb * 32) * 2, voff, w);
+                store_bf16_hi(out0 + ((long)(rr + 1) * d2 + nb * 32) * 2, voff, w);
+            }
         }
+    }
     if (MODE == MODE_DQ || MODE == MODE_DK) {
         const bf16_t* W = reinterpret_cast<const bf16_t*>(a.dotwith);
 #pragma unroll
