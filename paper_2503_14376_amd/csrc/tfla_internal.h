@@ -89,7 +89,6 @@ template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int d
 // prologue, epilogue and barriers); bf16, d1 = 512: the X fragments alone take 128 registers, so one
 // workgroup per CU with a 256-wide block; fp32: what the generic kernel's register budget allows.
 inline int tile_bd2(int d1, int d2, int dtype) {
-    if (dtype == 1 && d1 > 256 && d2 % 256 == 0) return 256;
     if (d2 % 128 == 0) return 128;
     return 64;
 }

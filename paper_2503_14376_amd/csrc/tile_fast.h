@@ -41,12 +41,17 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     constexpr int NKS = D1 / BCS;
     static_assert(BD2 * BCS * 2 <= STAGE && BCS <= 64 && D1 % BCS == 0, "state slice must fit a stage");
 
-    __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
+    // after the loops the ring's memory holds the output block (and the dot operand) of each wave
+    constexpr int EPI = ((MODE == MODE_DQ || MODE == MODE_DK) ? 2 : 1) * NW * 32 * BD2 * 2;
+    constexpr int SMEM = NS * STAGE > EPI ? NS * STAGE : EPI;
+    static_assert(SMEM <= BUDGET, "LDS budget");
+    __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     __shared__ __attribute__((aligned(256))) float ldsW[NS][NW][64];   // column weights of a tile, one copy per wave
-    __shared__ float ldsR[NW * 32];
-    __shared__ float ldsS[BR];                       // inter-chunk row scale of the workgroup's rows
-    __shared__ float ldsM[(MODE == MODE_H) ? BR : 1];  // their max state (mLSTMexp forward)
-    __shared__ float ldsN[(MODE == MODE_H) ? D1 : 1];
+    // per-row scalars of each wave's 32 rows (two copies side by side), fetched like the tiles
+    __shared__ __attribute__((aligned(256))) float ldsS[NW][64];    // inter-chunk row scale
+    __shared__ __attribute__((aligned(256))) float ldsWr[NW][64];   // row term of the weights
+    __shared__ __attribute__((aligned(256))) float ldsM[(MODE == MODE_H) ? NW : 1][64];  // max state (mLSTMexp forward)
+    __shared__ __attribute__((aligned(256))) float ldsN[(MODE == MODE_H) ? D1 : 64];     // n_{k-1}
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     TFLA_TL(0);
@@ -107,24 +112,23 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks) xf[ks] = E::load(xr + 16 * ks);
     }
-    const float wr = a.wrow[tbase + wr0 + l32];
+    {
+        const uint32_t vo = (uint32_t)(lane & 31) * 4u;
+        dma4(a.srow + tbase + wr0, vo, lds_addr(&ldsS[wave][0]));
+        dma4(a.wrow + tbase + wr0, vo, lds_addr(&ldsWr[wave][0]));
+        if (MODE == MODE_H) {
+            if (a.variant == 0) {
+                dma4(a.mout + tbase + wr0, vo, lds_addr(&ldsM[wave][0]));
+                for (int c = wave; c < D1 / 64; c += NW)
+                    dma4(a.nstate + ((long)bh * a.Nc + kc) * D1 + 64 * c, (uint32_t)lane * 4u, lds_addr(&ldsN[64 * c]));
+            }
+        }
+    }
 #pragma unroll
     for (int p = 0; p < NS - 1; ++p)
         if (p < NI) issue(p);
-    // (after the ring's first loads are on their way: the LDS writes below wait for their data)
-    if (tid < BR) {
-        ldsS[tid] = a.srow[tbase + r0 + tid];
-        if (MODE == MODE_H) ldsM[tid] = (a.variant == 0) ? a.mout[tbase + r0 + tid] : 0.0f;
-    }
-    if (MODE == MODE_H) {
-        if (a.variant == 0)
-            for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * D1 + i];
-    }
-    // make the plain loads above complete before the ring's wait counts are relied upon; the empty
-    // asm makes the compiler place its own wait for wr here rather than at its first use inside the
-    // tile loop, where it would drain the ring on every pass
+    // everything above must have landed before the ring's wait counts are relied upon
     wait_vmcnt<0>();
-    asm volatile("" ::"v"(wr));
     __syncthreads();
     TFLA_TL(1);
 
@@ -155,7 +159,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
             for (int ks = 0; ks < BCS / 16; ++ks)
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(xf[i * (BCS / 16) + ks], b[ks][nb], acc[nb]);
+                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks][nb], xf[i * (BCS / 16) + ks], acc[nb]);
             constexpr int PF = NF < 4 ? NF : 4;
 #pragma unroll
             for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
@@ -169,15 +173,13 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         }
     }
     TFLA_TL(2);
-    {
-        float sr[16];
+    // The accumulators are kept transposed (rows = columns of the output block, columns = the
+    // wave's 32 output rows): every per-row quantity is then one scalar per lane.
+    const float srl = ldsS[wave][l32];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sr[v] = ldsS[wave * 32 + acc_row(v, g)];
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[nb][v] *= sr[v];
-    }
+        for (int v = 0; v < 16; ++v) acc[nb][v] *= srl;
     float nrm = 0.0f;
     if (MODE == MODE_H) {
         if (a.variant == 0) {
@@ -187,11 +189,12 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dot += E::frag_elem(xf[ks], e) * ldsN[16 * ks + 8 * g + e];
             dot += __shfl_xor(dot, 32, 64);
-            nrm = dot * ldsS[wave * 32 + l32];
+            nrm = dot * srl;
         }
     }
     TFLA_TL(3);
     // ---------------- intra-chunk part, one 32-column tile per item
+    const float wr = ldsWr[wave][l32];
     float rowsum = 0.0f;
     for (int ct = ct_lo; ct < ct_hi; ++ct) {
         const int i = NKS + ct - ct_lo;
@@ -252,8 +255,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             }
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                acc[nb] = E::mma(p0, z[nb][0], acc[nb]);
-                acc[nb] = E::mma(p1, z[nb][1], acc[nb]);
+                acc[nb] = E::mma(z[nb][0], p0, acc[nb]);
+                acc[nb] = E::mma(z[nb][1], p1, acc[nb]);
             }
             // every Z fragment pair costs four transposing reads; keep two pairs ahead
             constexpr int PF = NB < 2 ? NB : 2;
@@ -271,53 +274,62 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 
     TFLA_TL(4);
     // ---------------- epilogue
-    float inv[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) inv[v] = 1.0f;
+    const long t = tbase + wr0 + l32;       // this lane's output row
+    float inv = 1.0f;
     if (MODE == MODE_H) {
         if (a.variant == 0) {
             rowsum += __shfl_xor(rowsum, 32, 64);
             nrm += rowsum;
-            const long t = tbase + wr0 + l32;
-            const float den = fmaxf(fabsf(nrm), expf(-ldsM[wave * 32 + l32])) + a.eps;
-            if (g == 0) {
-                ldsR[wave * 32 + l32] = 1.0f / den;
-                if (a.nout && nb2 == 0) a.nout[t] = nrm;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int v = 0; v < 16; ++v) inv[v] = ldsR[wave * 32 + acc_row(v, g)];
+            const float den = fmaxf(fabsf(nrm), expf(-ldsM[wave][l32])) + a.eps;
+            inv = 1.0f / den;
+            if (g == 0 && a.nout && nb2 == 0) a.nout[t] = nrm;
         }
     }
-    // Output rows: registers v, v+1 of a lane are consecutive rows of one column.  Row addresses
-    // are formed on the scalar unit (uniform base per row) plus one per-lane offset, and two rows
-    // share one packed conversion.
+    // Register quad 4j..4j+3 of block nb holds columns 32 nb + 8 j + 4 g + {0..3} of row t.  The
+    // output block goes through LDS (the ring is free now) so that it leaves in full 16-byte,
+    // row-contiguous stores: per wave a [32][BD2] bf16 tile with XOR-swizzled 16-byte chunks.
+    barrier_nofence();                                   // every wave is done reading the ring
+    constexpr int OCPR = BD2 / 8, ORB = BD2 * 2;         // chunks and bytes per tile row
+    char* otile = smem + wave * (32 * ORB);
+    char* wtile = smem + NW * (32 * ORB) + wave * (32 * ORB);
+    DmaTile<32, BD2, 64, SWZ_K> dw;                      // this wave's rows of the dot operand
+    if (MODE == MODE_DQ || MODE == MODE_DK) {
+        dw.init(d2, lane);
+        dw.issue(reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2, lds_addr(wtile), lane);
+    }
+    const int fsw = swz_mask<SWZ_K, OCPR>(l32);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint2 w;
+            w.x = pack_bf16x2(acc[nb][4 * j] * inv, acc[nb][4 * j + 1] * inv);
+            w.y = pack_bf16x2(acc[nb][4 * j + 2] * inv, acc[nb][4 * j + 3] * inv);
+            *reinterpret_cast<uint2*>(otile + l32 * ORB + (((4 * nb + j) ^ fsw) * 16) + 8 * g) = w;
+        }
     {
-        char* out0 = reinterpret_cast<char*>(a.Out) + ((tbase + wr0) * d2 + (long)nb2 * BD2) * 2;
-        const uint32_t voff = (uint32_t)((4 * g * d2 + l32) * 2);
+        char* obase = reinterpret_cast<char*>(a.Out) + ((tbase + wr0) * d2 + (long)nb2 * BD2) * 2;
+        constexpr int RPI = 64 / OCPR;                   // tile rows covered by one 64-lane store
 #pragma unroll
-        for (int v = 0; v < 16; v += 2) {
-            const int rr = 8 * (v >> 2) + (v & 3);     // row of register v for lane group 0
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const uint32_t w = pack_bf16x2(acc[nb][v] * inv[v], acc[nb][v + 1] * inv[v + 1]);
-                store_bf16_lo(out0 + ((long)rr * d2 + nb * 32) * 2, voff, w);
-                store_bf16_hi(out0 + ((long)(rr + 1) * d2 + nb * 32) * 2, voff, w);
-            }
+        for (int q = 0; q < 32 / RPI; ++q) {
+            const int r = q * RPI + lane / OCPR, c = lane % OCPR;
+            const u32x4 w = *reinterpret_cast<const u32x4*>(otile + r * ORB + ((c ^ swz_mask<SWZ_K, OCPR>(r)) * 16));
+            *reinterpret_cast<u32x4*>(obase + (long)r * d2 * 2 + c * 16) = w;
         }
     }
     if (MODE == MODE_DQ || MODE == MODE_DK) {
-        const bf16_t* W = reinterpret_cast<const bf16_t*>(a.dotwith);
+        wait_vmcnt<0>();                                 // the dot operand has landed (and the stores are out)
+        float d = 0.0f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const long t = tbase + wr0 + acc_row(v, g);
-            float d = 0.0f;
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                d += acc[nb][v] * E::to_f32(W[t * d2 + (long)nb2 * BD2 + nb * 32 + l32]);
-            d = half_sum(d);
-            if (l32 == 0) a.dotpart[(long)nb2 * ((long)gridDim.z / a.Nc) * a.T + t] = d;
-        }
+            for (int j = 0; j < 4; ++j) {
+                const uint2 w = *reinterpret_cast<const uint2*>(wtile + l32 * ORB + (((4 * nb + j) ^ fsw) * 16) + 8 * g);
+                d += acc[nb][4 * j] * bf16_lo_to_f32(w.x) + acc[nb][4 * j + 1] * bf16_hi_to_f32(w.x) +
+                     acc[nb][4 * j + 2] * bf16_lo_to_f32(w.y) + acc[nb][4 * j + 3] * bf16_hi_to_f32(w.y);
+            }
+        d += __shfl_xor(d, 32, 64);
+        if (g == 0) a.dotpart[(long)nb2 * ((long)gridDim.z / a.Nc) * a.T + t] = d;
     }
     TFLA_TL(5);
 #ifdef TFLA_TIMELINE

@@ -5,8 +5,10 @@
 #endif
 #include "tile.hip"
 
-#if defined(TFLA_TIMELINE) && TFLA_TILE_MODE == 0
-extern "C" __attribute__((visibility("default"))) int tfla_debug_timeline(unsigned long long* host, size_t n) {
+#if defined(TFLA_TIMELINE)
+#define TFLA_CAT2(a, b) a##b
+#define TFLA_CAT(a, b) TFLA_CAT2(a, b)
+extern "C" __attribute__((visibility("default"))) int TFLA_CAT(tfla_debug_timeline_mode, TFLA_TILE_MODE)(unsigned long long* host, size_t n) {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(tfla::tfla_timeline), n * sizeof(unsigned long long));
 }
 #endif
