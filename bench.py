@@ -50,6 +50,37 @@ def algorithmic_flops(w: wl.Workload, F_causal: float = 0.5):
     return fl, fwd, bwd
 
 
+def algorithmic_bytes(w: wl.Workload, es: int):
+    """HBM bytes each kernel must move per launch if every operand is read once and every result
+    written once: the sequence operands, one set of chunk states (stored in the element type of
+    q/k/v), the output block.  Gate vectors (a few fp32 per token) are included."""
+    tok = w.B * w.NH * w.T
+    st = w.B * w.NH * (w.T // w.chunk) * w.dqk * w.dhv * es
+    g = tok * 4
+    rec = tok * (w.dqk + w.dhv) * es + st + 2 * g
+    return {
+        "recurrent_fwd": rec,
+        "recurrent_bwd": rec,
+        "tile_H": tok * (2 * w.dqk + w.dhv) * es + st + tok * w.dhv * es + 4 * g,
+        "tile_dV": tok * (2 * w.dqk + w.dhv) * es + st + tok * w.dhv * es + 3 * g,
+        "tile_dQ": tok * (2 * w.dhv + 2 * w.dqk) * es + st + tok * w.dqk * es + 4 * g,
+        "tile_dK": tok * (2 * w.dhv + 2 * w.dqk) * es + st + tok * w.dqk * es + 4 * g,
+    }
+
+
+# HBM bytes per launch (fetched + written) of each kernel at the default workload (c4, chunk 256,
+# exponential gate), from rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script with
+# --calibrate-copy, each scaled by what the same counter reads for the 1 GiB copy kernel
+# (profiles/hbm_traffic_c4.txt).  Reported as roofline.traffic only for that workload.
+MEASURED_TRAFFIC_C4 = {
+    "recurrent_kernel": 202.2e6 + 184.7e6,
+    "tile_kernel<H>": 405.5e6 + 134.8e6,
+    "tile_kernel<dV>": 406.7e6 + 134.2e6,
+    "tile_kernel<dQ>": 538.6e6 + 68.2e6,
+    "tile_kernel<dK>": 538.6e6 + 68.2e6,
+}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +93,9 @@ def main() -> int:
     ap.add_argument("--fwd-only", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy kernel (the known-size reference that the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards over batch and heads without "
@@ -106,6 +140,13 @@ def main() -> int:
                            fo["m_out"], dev.get("C0"), dev.get("n0"), dev.get("m0"), None, chunk=w.chunk,
                            variant=w.variant, eps=1e-6, workspace=ws_b, out=bo)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -119,7 +160,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kernels = {}
+    kernels, prof = {}, {}
     if use_events:
         prof = tfla.profile_read()
         tfla.profile_enable(0)
@@ -133,18 +174,48 @@ def main() -> int:
 
     roof = None
     if kernels:
-        cand = {k_: v_ for k_, v_ in kernels.items() if k_ in fl}
-        dom = max(cand, key=cand.get)
-        ach = fl[dom] / (cand[dom] * 1e-3)
-        roof = {"bound": "mfma", "kernel": dom, "achieved": ach / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
-                "frac": ach / peak, "traffic": None,
-                "kernel_ms": {k_: round(v_, 4) for k_, v_ in kernels.items()},
-                "kernel_frac": {k_: fl[k_] / (v_ * 1e-3) / peak for k_, v_ in cand.items()}}
+        es = 2 if w.dtype == wl.BF16 else 4
+        byts = algorithmic_bytes(w, es)
+        # a kernel symbol may be launched several times per step (the recurrent kernel runs forward,
+        # forward again inside the backward call, and reversed): group the event families by symbol
+        groups = {"recurrent_kernel": ["recurrent_fwd", "recurrent_bwd"], "tile_kernel<H>": ["tile_H"],
+                  "tile_kernel<dV>": ["tile_dV"], "tile_kernel<dQ>": ["tile_dQ"], "tile_kernel<dK>": ["tile_dK"]}
+        per = {}
+        for sym, fams in groups.items():
+            fams = [f for f in fams if f in prof and prof[f]["launches"] > 0]
+            if not fams:
+                continue
+            n = sum(prof[f]["launches"] for f in fams)
+            ms = sum(prof[f]["ms"] for f in fams)
+            avg_s = ms / n * 1e-3
+            flops = sum(fl[f] * prof[f]["launches"] for f in fams) / n
+            bts = sum(byts[f] * prof[f]["launches"] for f in fams) / n
+            per[sym] = {"launches_per_step": n / args.steps, "avg_ms": ms / n, "total_ms_per_step": ms / args.steps,
+                        "flops": flops, "bytes": bts, "tflops": flops / avg_s / 1e12, "gbs": bts / avg_s / 1e9,
+                        "mfma_frac": flops / avg_s / peak, "hbm_frac": bts / avg_s / PEAK_HBM}
+        dom = max(per, key=lambda k_: per[k_]["total_ms_per_step"])
+        pd = per[dom]
+        # the roofline that binds a kernel is the one with the larger floor time
+        hbm_bound = pd["bytes"] / PEAK_HBM > pd["flops"] / peak
+        traffic = None
+        if (w.name, w.chunk, w.variant) == ("c4", 256, wl.EXP) and dom in MEASURED_TRAFFIC_C4:
+            traffic = MEASURED_TRAFFIC_C4[dom]
+        roof = {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom,
+                "achieved": pd["gbs"] if hbm_bound else pd["tflops"],
+                "peak": PEAK_HBM / 1e9 if hbm_bound else peak / 1e12,
+                "unit": "GB/s" if hbm_bound else "TFLOP/s",
+                "frac": pd["hbm_frac"] if hbm_bound else pd["mfma_frac"],
+                "traffic": traffic,
+                "avg_launch_ms": pd["avg_ms"], "algorithmic_bytes_per_launch": pd["bytes"],
+                "algorithmic_flops_per_launch": pd["flops"],
+                "kernels": {k_: {m_: (round(x_, 5) if isinstance(x_, float) and x_ < 1e6 else x_) for m_, x_ in v_.items()}
+                            for k_, v_ in per.items()},
+                "kernel_ms": {k_: round(v_, 4) for k_, v_ in kernels.items()}}
 
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import mlstm_oracle as orc
-        nsl = min(4, w.B * w.NH)
+        nsl = min(16, w.B * w.NH)
         ds = wl.make_inputs(w, heads=nsl)
         oi = gu.oracle_inputs(ds)
         c0 = time.perf_counter()
@@ -160,7 +231,8 @@ def main() -> int:
                                                                    " + fp64 chunkwise backward (numpy)" if do_bwd else "")}
 
     line = {
-        "metric": "mLSTM fwd+bwd tokens/s" if do_bwd else "mLSTM fwd tokens/s",
+        "metric": ("mLSTM fwd+bwd tokens/s and % bf16 MFMA peak at T=8192, NH=8, dqk=256, dhv=512" if do_bwd
+                   else "mLSTM fwd tokens/s"),
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == wl.BF16 else "f32", "data": "synthetic",

@@ -1,0 +1,143 @@
+"""Host-side tests of the C-ABI library: it loads, exports every entry point the header
+declares, and rejects invalid arguments with the documented codes before anything is launched.
+No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tfla_mlstm.h")
+
+
+@pytest.fixture(scope="module")
+def tfla():
+    import paper_2503_14376_amd as pkg
+    if not os.path.exists(pkg.lib_path()):
+        from paper_2503_14376_amd import build
+        build.build(verbose=False)
+    pkg.load_library()
+    return pkg
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"TFLA_API\s+[\w\s\*]+?\b(tfla_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_entry_points():
+    names = declared_symbols()
+    for need in ("tfla_mlstm_fwd", "tfla_mlstm_bwd", "tfla_mlstm_workspace_bytes", "tfla_mlstm_check"):
+        assert need in names, names
+
+
+def test_library_exports_every_declared_symbol(tfla):
+    lib = ctypes.CDLL(tfla.lib_path())
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+    from paper_2503_14376_amd import binding
+    assert sorted(binding.EXPORTS) == declared_symbols()
+
+
+def test_missing_library_fails_loudly(tfla, monkeypatch):
+    from paper_2503_14376_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libtfla_mlstm.so")
+    with pytest.raises(ImportError):
+        binding.load_library()
+
+
+OK_ARGS = dict(direction=0, B=2, NH=8, T=8192, dqk=256, dhv=512, chunk=256, variant=0, dtype=1)
+
+
+def _check(tfla, **kw):
+    a = dict(OK_ARGS); a.update(kw)
+    return tfla.check(a["direction"], a["B"], a["NH"], a["T"], a["dqk"], a["dhv"], a["chunk"], a["variant"], a["dtype"])
+
+
+def test_check_accepts_the_benchmark_configurations(tfla):
+    import workloads as wl
+    for w in wl.CONFIGS.values():
+        for direction in (0, 1):
+            assert tfla.check(direction, w.B, w.NH, w.T, w.dqk, w.dhv, w.chunk, w.variant, w.dtype) == 0, w.name
+            assert tfla.workspace_bytes(direction, w.B, w.NH, w.T, w.dqk, w.dhv, w.chunk, w.variant, w.dtype) > 0
+    for L in wl.C2_CHUNKS:
+        assert _check(tfla, variant=1, chunk=L) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), -2), (dict(NH=-1), -2), (dict(T=0), -2), (dict(dqk=96), -2), (dict(dhv=1024), -2),
+    (dict(dtype=0, dhv=512), -2), (dict(B=4096, NH=16), -2),
+    (dict(chunk=0), -3), (dict(chunk=32), -3), (dict(chunk=96), -3), (dict(chunk=4096), -3),
+    (dict(T=8192 + 64, chunk=256), -3), (dict(T=64 * 8192, chunk=64), -3),
+    (dict(variant=2), -4), (dict(dtype=7), -4), (dict(direction=3), -4),
+])
+def test_check_rejects_invalid_dimensions(tfla, kw, code):
+    assert _check(tfla, **kw) == code
+    a = dict(OK_ARGS); a.update(kw)
+    assert tfla.workspace_bytes(*[a[k] for k in ("direction", "B", "NH", "T", "dqk", "dhv", "chunk", "variant", "dtype")]) == 0
+
+
+def test_status_strings(tfla):
+    seen = set()
+    for code in range(0, -7, -1):
+        s = tfla.status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert tfla.status_string(-99)      # unknown codes still give a printable string
+    assert tfla.load_library().tfla_version() >= 1
+
+
+def test_workspace_grows_with_the_problem(tfla):
+    small = tfla.workspace_bytes(1, 1, 1, 512, 64, 64, 64, 0, 1)
+    big = tfla.workspace_bytes(1, 2, 8, 8192, 256, 512, 256, 0, 1)
+    assert 0 < small < big
+    # the backward workspace holds both chunk-state sets (bf16): at least 2 * BH*Nc*dqk*dhv*2 bytes
+    assert big >= 2 * 16 * 32 * 256 * 512 * 2
+    assert big % 256 == 0
+
+
+def _call_fwd(lib, q=1, k=1, v=1, i=1, f=1, C0=0, n0=0, m0=0, H=1, ws=256, ws_bytes=1 << 40, **kw):
+    """tfla_mlstm_fwd with fake (never dereferenced) pointers: only the host-side validation runs."""
+    a = dict(OK_ARGS); a.update(kw)
+    P = lambda x: ctypes.c_void_p(x * 4096) if x else None
+    return lib.tfla_mlstm_fwd(P(q), P(k), P(v), P(i), P(f), P(C0), P(n0), P(m0), a["B"], a["NH"], a["T"], a["dqk"],
+                              a["dhv"], a["chunk"], a["variant"], a["dtype"], 1e-6, P(H), None, None, None, None, None,
+                              ctypes.c_void_p(ws) if ws else None, ws_bytes, None)
+
+
+def test_forward_argument_validation_happens_before_any_launch(tfla):
+    lib = tfla.load_library()
+    assert _call_fwd(lib, q=0) == -1
+    assert _call_fwd(lib, H=0) == -1
+    assert _call_fwd(lib, f=0) == -1
+    assert _call_fwd(lib, dqk=100) == -2
+    assert _call_fwd(lib, chunk=100) == -3
+    assert _call_fwd(lib, variant=5) == -4
+    assert _call_fwd(lib, C0=1) == -6              # initial state only partly given
+    assert _call_fwd(lib, C0=1, n0=1) == -6
+    assert _call_fwd(lib, ws=0) == -5              # no workspace
+    assert _call_fwd(lib, ws=4096 + 8) == -5       # misaligned workspace
+    assert _call_fwd(lib, ws=4096, ws_bytes=1024) == -5   # too small
+
+
+def test_backward_argument_validation_happens_before_any_launch(tfla):
+    lib = tfla.load_library()
+    P = lambda x: ctypes.c_void_p(x * 4096) if x else None
+    a = OK_ARGS
+
+    def call(n_out=1, m_out=1, dH=1, dq=1, d_f=1, C0=0, ws=4096, ws_bytes=1 << 40, chunk=256, variant=0):
+        return lib.tfla_mlstm_bwd(P(1), P(1), P(1), P(1), P(1), P(C0), None, None, P(n_out), P(m_out), P(dH), None,
+                                  a["B"], a["NH"], a["T"], a["dqk"], a["dhv"], chunk, variant, a["dtype"], 1e-6,
+                                  P(dq), P(1), P(1), P(1), P(d_f), None, P(1) if ws else None, ws_bytes, None)
+    assert call(dH=0) == -1
+    assert call(dq=0) == -1
+    assert call(d_f=0) == -1
+    assert call(n_out=0) == -1                     # the exponential-gate backward needs n and m of the forward
+    assert call(m_out=0) == -1
+    assert call(chunk=48) == -3
+    assert call(C0=1) == -6
+    assert call(ws=0) == -5
+    assert call(ws_bytes=4096) == -5
