@@ -91,6 +91,8 @@ def main() -> int:
     ap.add_argument("--variant", default="")
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--fwd-only", action="store_true")
+    ap.add_argument("--recompute", action="store_true",
+                    help="do not hand the forward workspace to the backward call (gates and chunk states are recomputed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -138,7 +140,8 @@ def main() -> int:
         if do_bwd:
             tfla.mlstm_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["dH"], fo["n_out"],
                            fo["m_out"], dev.get("C0"), dev.get("n0"), dev.get("m0"), None, chunk=w.chunk,
-                           variant=w.variant, eps=1e-6, workspace=ws_b, out=bo)
+                           variant=w.variant, eps=1e-6, workspace=ws_b, out=bo,
+                           fwd_workspace=None if args.recompute else ws_f)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()

@@ -70,7 +70,10 @@ enum {
  *        optional n_out, m_out (B, NH, T): the signed normaliser n_t^T q~_t and the max state
  *        m_t of every step, which tfla_mlstm_bwd needs for TFLA_EXP.
  *   workspace: device scratch of at least tfla_mlstm_workspace_bytes(TFLA_FWD, ...) bytes,
- *        256-byte aligned; its contents are undefined afterwards.
+ *        256-byte aligned.  Afterwards it holds, in a layout private to the library, what the
+ *        backward pass can reuse (the gate vectors, the chunk states C_{k-1} of Sec. 2.2 and
+ *        C_T): a caller that keeps it untouched until the matching tfla_mlstm_bwd call may pass
+ *        it there as fwd_workspace; a caller that does not may overwrite or free it.
  */
 TFLA_API int tfla_mlstm_fwd(const void* q, const void* k, const void* v,
                    const float* i_pre, const float* f_pre,
@@ -92,9 +95,14 @@ TFLA_API int tfla_mlstm_fwd(const void* q, const void* k, const void* v,
  *        dCn (B, NH, dqk, dhv) gradient w.r.t. the returned final state, or NULL for zero.
  *   out: dq, dk (B, NH, T, dqk), dv (B, NH, T, dhv) in `dtype`; d_i_pre, d_f_pre (B, NH, T)
  *        float; dC0 (B, NH, dqk, dhv) float or NULL.  No gradient is produced for n0, m0.
- *   workspace: at least tfla_mlstm_workspace_bytes(TFLA_BWD, ...) bytes, 256-byte aligned.
- *        The chunk states are recomputed inside this call; nothing but n_out/m_out has to be
- *        kept from the forward call.
+ *   fwd_workspace, fwd_workspace_bytes: NULL / 0, or the workspace of the forward call with
+ *        exactly these inputs, dimensions, chunk, variant and dtype, unmodified since that call
+ *        (read only here).  With NULL the gate vectors and the chunk states are recomputed
+ *        inside this call, and nothing but n_out/m_out has to be kept from the forward call
+ *        (App. B.3 leaves open whether states are stored or recomputed; both are offered).
+ *        With a forward workspace the results are the same and the recomputation is skipped.
+ *   workspace: at least tfla_mlstm_workspace_bytes(TFLA_BWD, ...) bytes, 256-byte aligned;
+ *        must not overlap fwd_workspace.
  */
 TFLA_API int tfla_mlstm_bwd(const void* q, const void* k, const void* v,
                    const float* i_pre, const float* f_pre,
@@ -105,6 +113,7 @@ TFLA_API int tfla_mlstm_bwd(const void* q, const void* k, const void* v,
                    int chunk, int variant, int dtype, float eps,
                    void* dq, void* dk, void* dv,
                    float* d_i_pre, float* d_f_pre, float* dC0,
+                   const void* fwd_workspace, size_t fwd_workspace_bytes,
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*

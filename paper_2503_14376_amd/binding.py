@@ -43,7 +43,7 @@ def load_library():
                                    vp, fp, fp, fp, fp, fp, vp, sz, vp]
     lib.tfla_mlstm_bwd.restype = ci
     lib.tfla_mlstm_bwd.argtypes = [vp, vp, vp, fp, fp, fp, fp, fp, fp, fp, vp, fp, ci, ci, ci, ci, ci, ci, ci, ci, cf,
-                                   vp, vp, vp, fp, fp, fp, vp, sz, vp]
+                                   vp, vp, vp, fp, fp, fp, vp, sz, vp, sz, vp]
     lib.tfla_mlstm_workspace_bytes.restype = sz
     lib.tfla_mlstm_workspace_bytes.argtypes = [ci] * 9
     lib.tfla_mlstm_check.restype = ci
@@ -154,8 +154,10 @@ def mlstm_fwd(q, k, v, i_pre, f_pre, C0=None, n0=None, m0=None, chunk=256, varia
 
 def mlstm_bwd(q, k, v, i_pre, f_pre, dH, n_out=None, m_out=None, C0=None, n0=None, m0=None, dCn=None,
               chunk=256, variant=EXP, eps=1e-6, want_dC0=True, workspace=None, stream=None,
-              out: Optional[Dict] = None) -> Dict:
-    """tfla_mlstm_bwd on torch device tensors.  Returns dq, dk, dv, d_i_pre, d_f_pre, dC0."""
+              out: Optional[Dict] = None, fwd_workspace=None) -> Dict:
+    """tfla_mlstm_bwd on torch device tensors.  Returns dq, dk, dv, d_i_pre, d_f_pre, dC0.
+    fwd_workspace: the (untouched) workspace tensor of the matching mlstm_fwd call, or None to
+    recompute gates and chunk states."""
     import torch
     lib = load_library()
     B, NH, T, dqk = q.shape
@@ -184,6 +186,7 @@ def mlstm_bwd(q, k, v, i_pre, f_pre, dH, n_out=None, m_out=None, C0=None, n0=Non
                             B, NH, T, dqk, dhv, int(chunk), int(variant), dtype, float(eps),
                             _ptr(o["dq"]), _ptr(o["dk"]), _ptr(o["dv"]), _ptr(o["d_i_pre"]), _ptr(o["d_f_pre"]),
                             _ptr(o.get("dC0")),
+                            _ptr(fwd_workspace), 0 if fwd_workspace is None else fwd_workspace.numel(),
                             _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream_handle(stream))
     if rc != 0:
         raise TflaError(rc, "tfla_mlstm_bwd")

@@ -57,8 +57,11 @@ struct Carver {
     }
 };
 
+// The forward workspace doubles as the record the backward call can reuse (gate vectors, the
+// chunk states C_{k-1} and the final state), so its layout is part of the library's contract
+// with itself: carve_fwd is the only place that defines it.
 struct FwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *nst;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *nst, *Cfin;
     void* stT;
     size_t bytes;
 };
@@ -69,6 +72,7 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
     w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
     w.gbar = c.take<float>(d.BH * d.Nc);
     w.nst = c.take<float>(d.BH * d.Nc * d.dqk);
+    w.Cfin = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
     w.stT = c.take_bytes((size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz);
     w.bytes = c.off;
     return w;
@@ -93,7 +97,9 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.cdot = c.take<float>(d.BH);
     w.Cfinal = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
     const size_t st = (size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz;
-    w.cN = c.take_bytes(st); w.dcT = c.take_bytes(st); w.dcN = c.take_bytes(st);
+    // bf16: C_{k-1} and dC_k, both as (d_hv, d_qk); fp32 additionally dC_k as (d_qk, d_hv)
+    w.cN = c.take_bytes(st); w.dcT = c.take_bytes(st);
+    w.dcN = d.dtype == TFLA_BF16 ? nullptr : c.take_bytes(st);
     w.bytes = c.off;
     return w;
 }
@@ -256,7 +262,7 @@ int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_p
     // 2. recurrent kernel: C_{k-1} (transposed, element type of q/k/v) and n_{k-1} for every chunk
     RecArgs r;
     r.X = k; r.Y = v; r.rs = w.aK; r.gbar = w.gbar; r.S0 = C0;
-    r.stT = w.stT; r.stN = nullptr; r.Sfinal = Cn;
+    r.stT = w.stT; r.stN = nullptr; r.Sfinal = Cn; r.Sfinal2 = w.Cfin;
     r.n0 = is_exp ? n0 : nullptr; r.nst = is_exp ? w.nst : nullptr; r.nfinal = is_exp ? nn : nullptr;
     r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
     TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
@@ -283,7 +289,8 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
                    const float* C0, const float* n0, const float* m0, const float* n_out, const float* m_out,
                    const void* dH, const float* dCn, int B, int NH, int T, int dqk, int dhv, int chunk,
                    int variant, int dtype, float eps, void* dq, void* dk, void* dv, float* d_i_pre,
-                   float* d_f_pre, float* dC0, void* workspace, size_t workspace_bytes, void* stream) {
+                   float* d_f_pre, float* dC0, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                   void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
     if (rc != TFLA_OK) return rc;
     if (!q || !k || !v || !i_pre || !f_pre || !dH || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
@@ -299,26 +306,52 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     if (workspace_bytes < w.bytes) return TFLA_ERR_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
+    // What the matching forward call left in its workspace (gate vectors, C_{k-1} for every chunk,
+    // C_T) is reused when the caller hands that workspace over; otherwise it is recomputed here.
+    FwdWs fw{};
+    const bool reuse = fwd_workspace != nullptr;
+    if (reuse) {
+        if ((reinterpret_cast<uintptr_t>(fwd_workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+        fw = carve_fwd(d, const_cast<void*>(fwd_workspace));
+        if (fwd_workspace_bytes < fw.bytes) return TFLA_ERR_WORKSPACE;
+    }
+    // the generic fp32 kernels read the states of dQ / dK as (d_qk, d_hv); the bf16 kernels read
+    // (d_hv, d_qk) everywhere, so only that layout is ever written on the bf16 path
+    const bool tonly = dtype == TFLA_BF16;
+    const bool reuse_states = reuse && tonly;
+    const float* wrow = reuse ? fw.wrow : w.wrow;
+    const float* ucol = reuse ? fw.ucol : w.ucol;
+    const float* sH = reuse ? fw.sH : w.sH;
+    const float* aK = reuse ? fw.aK : w.aK;
+    const float* gbar = reuse ? fw.gbar : w.gbar;
+
     // 1. gates as in the forward pass, then fold 1/h_denom into the backward weights
-    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, s);
-    if (st != TFLA_OK) return st;
+    if (!reuse) {
+        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, s);
+        if (st != TFLA_OK) return st;
+    }
     GateBwdPrepArgs p;
-    p.wrow = w.wrow; p.sH = w.sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
+    p.wrow = wrow; p.sH = sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
     p.n = d.BHT; p.variant = variant; p.eps = eps;
     TFLA_LAUNCH(K_BWD_PREP, launch_gate_bwd_prep(p, s));
 
-    // 2. recompute the chunk states C_{k-1} (layout d_qk x d_hv, read by the dQ kernel)
-    RecArgs r;
-    r.X = k; r.Y = v; r.rs = w.aK; r.gbar = w.gbar; r.S0 = C0;
-    r.stT = nullptr; r.stN = w.cN; r.Sfinal = dCn ? w.Cfinal : nullptr;
-    r.n0 = nullptr; r.nst = nullptr; r.nfinal = nullptr;
-    r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
-    TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
+    // 2. the chunk states C_{k-1}
+    const void* cstates = reuse_states ? fw.stT : w.cN;
+    const float* Cfinal = reuse_states ? fw.Cfin : w.Cfinal;
+    if (!reuse_states) {
+        RecArgs r;
+        r.X = k; r.Y = v; r.rs = aK; r.gbar = gbar; r.S0 = C0;
+        r.stT = tonly ? w.cN : nullptr; r.stN = tonly ? nullptr : w.cN;
+        r.Sfinal = dCn ? w.Cfinal : nullptr; r.Sfinal2 = nullptr;
+        r.n0 = nullptr; r.nst = nullptr; r.nfinal = nullptr;
+        r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
+        TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
+    }
 
-    // 3. backward recurrence: dC_k for every chunk (both layouts), dC_0 at the end
+    // 3. backward recurrence: dC_k for every chunk, dC_0 at the end
     RecArgs rb;
-    rb.X = q; rb.Y = dH; rb.rs = w.sQ; rb.gbar = w.gbar; rb.S0 = dCn;
-    rb.stT = w.dcT; rb.stN = w.dcN; rb.Sfinal = dC0;
+    rb.X = q; rb.Y = dH; rb.rs = w.sQ; rb.gbar = gbar; rb.S0 = dCn;
+    rb.stT = w.dcT; rb.stN = tonly ? nullptr : w.dcN; rb.Sfinal = dC0; rb.Sfinal2 = nullptr;
     rb.n0 = nullptr; rb.nst = nullptr; rb.nfinal = nullptr;
     rb.T = T; rb.L = chunk; rb.Nc = d.Nc; rb.d1 = dqk; rb.d2 = dhv; rb.reverse = 1;
     TFLA_LAUNCH(K_REC_BWD, launch_recurrent(rb, (int)d.BH, dtype, s));
@@ -328,20 +361,20 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
     t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr;
     // dV: rows = kv index j
-    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = w.ucol; t.wcol = w.wrowB; t.srow = w.aK; t.St = w.dcT;
+    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = w.dcT;
     t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
     TFLA_LAUNCH(K_TILE_DV, launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
     // dQ: rows = query index i
-    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = w.wrowB; t.wcol = w.ucol; t.srow = w.sQ; t.St = w.cN;
+    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = w.wrowB; t.wcol = ucol; t.srow = w.sQ; t.St = cstates;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = q; t.dotpart = w.partQ;
     TFLA_LAUNCH(K_TILE_DQ, launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
     // dK: rows = kv index j
-    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = w.ucol; t.wcol = w.wrowB; t.srow = w.aK; t.St = w.dcN;
+    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = tonly ? w.dcT : w.dcN;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = k; t.dotpart = w.partK;
     TFLA_LAUNCH(K_TILE_DK, launch_tile_mode<MODE_DK>(t, (int)d.BH, dtype, s));
 
     // 5. gate gradients
-    if (dCn) TFLA_LAUNCH(K_STATE_DOT, launch_state_dot(w.Cfinal, dCn, w.cdot, (long)dqk * dhv, (int)d.BH, s));
+    if (dCn) TFLA_LAUNCH(K_STATE_DOT, launch_state_dot(Cfinal, dCn, w.cdot, (long)dqk * dhv, (int)d.BH, s));
     GateGradArgs gg;
     gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
     gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;

@@ -173,7 +173,7 @@ __global__ void __launch_bounds__(256) recurrent_kernel(RecArgs a) {
         }
     }
     // ---- final state
-    if (a.Sfinal) {
+    if (a.Sfinal || a.Sfinal2) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -182,7 +182,11 @@ __global__ void __launch_bounds__(256) recurrent_kernel(RecArgs a) {
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + wm * 32 * MI + 32 * mi + acc_row(v, g);
                     const int n = n0 + wn * 32 * NI + 32 * ni + l32;
-                    a.Sfinal[((long)bh * a.d1 + m) * a.d2 + n] = acc[mi][ni][v];
+                    {
+                    const long o = ((long)bh * a.d1 + m) * a.d2 + n;
+                    if (a.Sfinal) a.Sfinal[o] = acc[mi][ni][v];
+                    if (a.Sfinal2) a.Sfinal2[o] = acc[mi][ni][v];
+                }
                 }
     }
     if (with_n && tid < BM && a.nfinal) a.nfinal[(long)bh * a.d1 + m0 + tid] = nacc;

@@ -200,7 +200,7 @@ __global__ void __launch_bounds__(WM * WN * 64) recurrent_kernel_bf16(RecArgs a)
         }
     }
     // ---- final state
-    if (a.Sfinal) {
+    if (a.Sfinal || a.Sfinal2) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -209,7 +209,11 @@ __global__ void __launch_bounds__(WM * WN * 64) recurrent_kernel_bf16(RecArgs a)
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + (wm * MI + mi) * 32 + acc_row(v, g);
                     const int n = n0 + (wn * NI + ni) * 32 + l32;
-                    a.Sfinal[((long)bh * a.d1 + m) * a.d2 + n] = acc[mi][ni][v];
+                    {
+                    const long o = ((long)bh * a.d1 + m) * a.d2 + n;
+                    if (a.Sfinal) a.Sfinal[o] = acc[mi][ni][v];
+                    if (a.Sfinal2) a.Sfinal2[o] = acc[mi][ni][v];
+                }
                 }
     }
     if (with_n && g == 0 && a.nfinal) {

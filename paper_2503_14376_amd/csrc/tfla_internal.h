@@ -57,6 +57,7 @@ struct RecArgs {
     void* stT;            // (BH, Nc, d2, d1) element type DT, or NULL
     void* stN;            // (BH, Nc, d1, d2) element type DT, or NULL
     float* Sfinal;        // (BH, d1, d2) fp32 or NULL
+    float* Sfinal2;       // second copy of the final state, or NULL
     const float* n0;      // (BH, d1) or NULL; normaliser vector, forward mLSTMexp only
     float* nst;           // (BH, Nc, d1) or NULL (NULL = no normaliser vector)
     float* nfinal;        // (BH, d1) or NULL

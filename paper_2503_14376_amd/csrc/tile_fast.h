@@ -7,6 +7,8 @@
 // the row index); the inter-chunk state is streamed through the same ring in [BD2][BCS]
 // slices before the column tiles.
 #pragma once
+#include <type_traits>
+
 #include "lds_tiles.h"
 #include "tfla_internal.h"
 
@@ -29,6 +31,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     using E = Elem<bf16_t>;
     using frag = E::frag;
     constexpr bool UPPER = (MODE & 1) != 0;
+    constexpr bool STT = (MODE == MODE_DQ || MODE == MODE_DK);   // state slices are contraction-major
     constexpr int NT = NW * 64, BR = NW * 32, BC = 32;
     constexpr int KS1 = D1 / 16, NB = BD2 / 32;
     constexpr int YB = BC * D1 * 2, ZB = BC * BD2 * 2, STAGE = YB + ZB;             // bytes
@@ -69,16 +72,19 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     const bf16_t* X = reinterpret_cast<const bf16_t*>(a.X);
     const bf16_t* Y = reinterpret_cast<const bf16_t*>(a.Y) + tbase * D1;
     const bf16_t* Z = reinterpret_cast<const bf16_t*>(a.Z) + tbase * d2 + (long)nb2 * BD2;
-    const bf16_t* St = reinterpret_cast<const bf16_t*>(a.St) + (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * D1;
+    const bf16_t* St = reinterpret_cast<const bf16_t*>(a.St) +
+                       (STT ? ((long)bh * a.Nc + kc) * D1 * d2 + (long)nb2 * BD2
+                            : (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * D1);
 
     const int ct_lo = UPPER ? r0 / BC : 0;
     const int ct_hi = UPPER ? a.L / BC : (r0 + BR) / BC;
     const int NI = NKS + (ct_hi - ct_lo);                       // items streamed through the ring
 
-    DmaTile<BD2, BCS, NT, SWZ_K> ds;  ds.init(D1, tid);
+    using DS = typename std::conditional<STT, DmaTile<BCS, BD2, NT, SWZ_T>, DmaTile<BD2, BCS, NT, SWZ_K>>::type;
+    DS ds;  ds.init(STT ? d2 : D1, tid);
     DmaTile<BC, D1, NT, SWZ_K> dy;    dy.init(D1, tid);
     DmaTile<BC, BD2, NT, SWZ_T> dz;   dz.init(d2, tid);
-    constexpr int CS = DmaTile<BD2, BCS, NT, SWZ_K>::N;
+    constexpr int CS = DS::N;
     constexpr int CT = DmaTile<BC, D1, NT, SWZ_K>::N + DmaTile<BC, BD2, NT, SWZ_T>::N + 1;
     const uint32_t smem_a = lds_addr(smem), w_a = lds_addr(ldsW);
     const float* wcol = a.wcol + tbase;
@@ -86,7 +92,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     auto issue = [&](int item) {
         const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
         if (item < NKS) {
-            ds.issue(St + item * BCS, st, tid);
+            ds.issue(St + (STT ? (long)item * BCS * d2 : (long)item * BCS), st, tid);
         } else {
             const int ct = ct_lo + item - NKS;
             dy.issue(Y + (long)ct * BC * D1, st, tid);
@@ -135,6 +141,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     KFragReader<BCS> rs_;  rs_.init(l32, g);
     KFragReader<D1> ry;    ry.init(l32, g);
     TFragReader<BD2> rz;   rz.init(lane, 4);
+    TFragReader<BD2> rzn;  rzn.init(lane, 8);    // natural k order, for contraction-major state slices
 
     f32x16 acc[NB];
 #pragma unroll
@@ -155,18 +162,20 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
             for (int ks = 0; ks < BCS / 16; ++ks)
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) b[ks][nb].v = rs_.load(sb, ks, nb);
+                for (int nb = 0; nb < NB; ++nb)
+                    b[ks][nb].v = STT ? rzn.load(sb, nb, 16 * ks, 16 * ks + 4) : rs_.load(sb, ks, nb);
 #pragma unroll
             for (int ks = 0; ks < BCS / 16; ++ks)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks][nb], xf[i * (BCS / 16) + ks], acc[nb]);
             constexpr int PF = NF < 4 ? NF : 4;
+            constexpr int DSR = STT ? 2 : 1;            // LDS reads per fragment
 #pragma unroll
-            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);
 #pragma unroll
             for (int q = 0; q < NF - PF; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);
             }
 #pragma unroll
             for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);

@@ -26,7 +26,15 @@ def run_case(w, with_dCn=False, heads=None, oracle_chunk=None):
     out = tfla.mlstm_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["dH"],
                          fwd["n_out"], fwd["m_out"], dev.get("C0"), dev.get("n0"), dev.get("m0"), dCn,
                          chunk=w.chunk, variant=w.variant, eps=1e-6)
+    # the same call with the forward call's workspace handed over (gates and chunk states reused
+    # instead of recomputed) must give the same numbers
+    out2 = tfla.mlstm_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["dH"],
+                          fwd["n_out"], fwd["m_out"], dev.get("C0"), dev.get("n0"), dev.get("m0"), dCn,
+                          chunk=w.chunk, variant=w.variant, eps=1e-6, fwd_workspace=fwd["workspace"])
     torch.cuda.synchronize()
+    for k_ in ("dq", "dk", "dv", "d_i_pre", "d_f_pre", "dC0"):
+        a_, b_ = out[k_].float(), out2[k_].float()
+        assert float((a_ - b_).abs().max()) <= 1e-6 * float(a_.abs().max()), k_
     oi = gu.oracle_inputs(d)
     ref = orc.chunkwise_bwd(**oi, dH=gu.flat(d["dH"]), dCn=None if dCn_np is None else gu.flat(dCn_np),
                             variant=w.variant, eps=1e-6, chunk=oracle_chunk or w.chunk)

@@ -93,7 +93,7 @@ def test_config4_forward_backward(name):
     dev = gu.dev_inputs(w, d)
     fwd = _run_fwd(w, dev)
     bwd = tfla.mlstm_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["dH"], fwd["n_out"], fwd["m_out"],
-                         chunk=w.chunk, variant=w.variant, eps=1e-6)
+                         chunk=w.chunk, variant=w.variant, eps=1e-6, fwd_workspace=fwd["workspace"])
     torch.cuda.synchronize()
     ds = wl.make_inputs(w, heads=NSAMPLE)
     oi = gu.oracle_inputs(ds)

@@ -128,10 +128,12 @@ def test_backward_argument_validation_happens_before_any_launch(tfla):
     P = lambda x: ctypes.c_void_p(x * 4096) if x else None
     a = OK_ARGS
 
-    def call(n_out=1, m_out=1, dH=1, dq=1, d_f=1, C0=0, ws=4096, ws_bytes=1 << 40, chunk=256, variant=0):
+    def call(n_out=1, m_out=1, dH=1, dq=1, d_f=1, C0=0, ws=4096, ws_bytes=1 << 40, chunk=256, variant=0,
+             fws=0, fws_bytes=0):
         return lib.tfla_mlstm_bwd(P(1), P(1), P(1), P(1), P(1), P(C0), None, None, P(n_out), P(m_out), P(dH), None,
                                   a["B"], a["NH"], a["T"], a["dqk"], a["dhv"], chunk, variant, a["dtype"], 1e-6,
-                                  P(dq), P(1), P(1), P(1), P(d_f), None, P(1) if ws else None, ws_bytes, None)
+                                  P(dq), P(1), P(1), P(1), P(d_f), None, P(fws) if fws else None, fws_bytes,
+                                  P(1) if ws else None, ws_bytes, None)
     assert call(dH=0) == -1
     assert call(dq=0) == -1
     assert call(d_f=0) == -1
@@ -141,3 +143,4 @@ def test_backward_argument_validation_happens_before_any_launch(tfla):
     assert call(C0=1) == -6
     assert call(ws=0) == -5
     assert call(ws_bytes=4096) == -5
+    assert call(fws=2, fws_bytes=1024) == -5       # a forward workspace that is too small to be one
