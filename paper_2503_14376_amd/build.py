@@ -15,7 +15,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-inline-asm", "-Wno-pass-failed"]
 
 # (source, object name, extra defines)
-UNITS = [("api.hip", "api.o", []), ("gates.hip", "gates.o", []), ("recurrent.hip", "recurrent.o", [])] + [
+# recurrent.hip: MFMA accumulators in ordinary VGPRs (the kernel also scales and stores them with
+# vector ALU instructions, which cannot read accumulation registers)
+UNITS = [("api.hip", "api.o", []), ("gates.hip", "gates.o", []),
+         ("recurrent.hip", "recurrent.o", ["-mllvm", "-amdgpu-mfma-vgpr-form"])] + [
     ("tile_inst.hip", "tile_mode%d.o" % m, ["-DTFLA_TILE_MODE=%d" % m]) for m in range(4)]
 
 

@@ -99,7 +99,8 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n) {
         TFLA_W(19) TFLA_W(20) TFLA_W(21) TFLA_W(22) TFLA_W(23) TFLA_W(24) TFLA_W(25) TFLA_W(26) TFLA_W(27)
         TFLA_W(28) TFLA_W(29) TFLA_W(30) TFLA_W(31) TFLA_W(32) TFLA_W(33) TFLA_W(34) TFLA_W(35) TFLA_W(36)
         TFLA_W(37) TFLA_W(38) TFLA_W(39) TFLA_W(40) TFLA_W(41) TFLA_W(42) TFLA_W(43) TFLA_W(44) TFLA_W(45)
-        TFLA_W(46) TFLA_W(47) TFLA_W(48)
+        TFLA_W(46) TFLA_W(47) TFLA_W(48) TFLA_W(49) TFLA_W(50) TFLA_W(51) TFLA_W(52) TFLA_W(53) TFLA_W(54)
+        TFLA_W(55) TFLA_W(56) TFLA_W(57) TFLA_W(58) TFLA_W(59) TFLA_W(60) TFLA_W(61) TFLA_W(62) TFLA_W(63)
 #undef TFLA_W
         default: wait_vmcnt<0>(); break;
     }

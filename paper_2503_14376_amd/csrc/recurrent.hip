@@ -200,19 +200,23 @@ static hipError_t launch_rec_t(const RecArgs& a, int BH, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int WM, int WN, int MI, int NI>
+template <int WN, int NI>
 static hipError_t launch_rec_bf16(const RecArgs& a, int BH, hipStream_t s) {
-    dim3 grid(a.d2 / (WN * 32 * NI), a.d1 / (WM * 32 * MI), BH);
-    hipLaunchKernelGGL((recurrent_kernel_bf16<WM, WN, MI, NI>), grid, dim3(WM * WN * 64), 0, s, a);
+    dim3 grid(a.d2 / (WN * 32 * NI), a.d1 / 64, BH);
+    hipLaunchKernelGGL((recurrent_kernel_bf16<WN, NI>), grid, dim3(WN * 64), 0, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_recurrent(const RecArgs& a, int BH, int dtype, hipStream_t s) {
-    // 128x128 state tiles when that still fills the chip, 64x64 tiles otherwise
+    if (dtype == 1) {
+        // the bf16 kernel writes the chunk states as (d2, d1) only
+        if (a.stN) return hipErrorInvalidValue;
+        return a.d2 % 128 == 0 ? launch_rec_bf16<4, 1>(a, BH, s) : launch_rec_bf16<2, 1>(a, BH, s);
+    }
+    // fp32: 128x128 state tiles when that still fills the chip, 64x64 tiles otherwise
     const bool big_ok = (a.d1 % 128 == 0) && (a.d2 % 128 == 0);
     const long wg_big = (long)BH * (a.d1 / 128) * (a.d2 / 128);
     const bool big = big_ok && wg_big >= 192;
-    if (dtype == 1) return big ? launch_rec_bf16<2, 4, 2, 1>(a, BH, s) : launch_rec_bf16<2, 2, 1, 1>(a, BH, s);
     return big ? launch_rec_t<float, 2, 2>(a, BH, s) : launch_rec_t<float, 1, 1>(a, BH, s);
 }
 
