@@ -200,10 +200,12 @@ static hipError_t launch_rec_t(const RecArgs& a, int BH, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int WN, int NI>
+template <int WN>
 static hipError_t launch_rec_bf16(const RecArgs& a, int BH, hipStream_t s) {
-    dim3 grid(a.d2 / (WN * 32 * NI), a.d1 / 64, BH);
-    hipLaunchKernelGGL((recurrent_kernel_bf16<WN, NI>), grid, dim3(WN * 64), 0, s, a);
+    dim3 grid(a.d2 / (WN * 32), a.d1 / 64, BH);
+    // pieces of 128 rows (half as many workgroup barriers) whenever the chunk size allows
+    if (a.L % 128 == 0) hipLaunchKernelGGL((recurrent_kernel_bf16<WN, 128>), grid, dim3(WN * 128), 0, s, a);
+    else hipLaunchKernelGGL((recurrent_kernel_bf16<WN, 64>), grid, dim3(WN * 128), 0, s, a);
     return hipGetLastError();
 }
 
@@ -211,7 +213,7 @@ hipError_t launch_recurrent(const RecArgs& a, int BH, int dtype, hipStream_t s) 
     if (dtype == 1) {
         // the bf16 kernel writes the chunk states as (d2, d1) only
         if (a.stN) return hipErrorInvalidValue;
-        return a.d2 % 128 == 0 ? launch_rec_bf16<4, 1>(a, BH, s) : launch_rec_bf16<2, 1>(a, BH, s);
+        return a.d2 % 128 == 0 ? launch_rec_bf16<4>(a, BH, s) : launch_rec_bf16<2>(a, BH, s);
     }
     // fp32: 128x128 state tiles when that still fills the chip, 64x64 tiles otherwise
     const bool big_ok = (a.d1 % 128 == 0) && (a.d2 % 128 == 0);
