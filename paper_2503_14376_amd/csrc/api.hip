@@ -61,7 +61,7 @@ struct Carver {
 // chunk states C_{k-1} and the final state), so its layout is part of the library's contract
 // with itself: carve_fwd is the only place that defines it.
 struct FwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *nst, *Cfin;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *nst, *Cfin;
     void* stT;
     size_t bytes;
 };
@@ -71,6 +71,7 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
     w.wrow = c.take<float>(d.BHT); w.ucol = c.take<float>(d.BHT); w.sH = c.take<float>(d.BHT);
     w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
     w.gbar = c.take<float>(d.BH * d.Nc);
+    w.csum = c.take<float>(2 * d.BH * d.Nc);
     w.nst = c.take<float>(d.BH * d.Nc * d.dqk);
     w.Cfin = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
     w.stT = c.take_bytes((size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz);
@@ -79,7 +80,8 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
 }
 
 struct BwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal;
+    double* bsum;
     void *cN, *dcT, *dcN;
     int nbQ, nbK;
     size_t bytes;
@@ -90,6 +92,8 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.wrow = c.take<float>(d.BHT); w.ucol = c.take<float>(d.BHT); w.sH = c.take<float>(d.BHT);
     w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
     w.gbar = c.take<float>(d.BH * d.Nc);
+    w.csum = c.take<float>(2 * d.BH * d.Nc);
+    w.bsum = c.take<double>(d.BH * ((d.T + 1023) / 1024));
     w.wrowB = c.take<float>(d.BHT); w.sQ = c.take<float>(d.BHT);
     w.nbQ = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype);
     w.nbK = w.nbQ;
@@ -159,12 +163,12 @@ void prof_collect() {
 }
 
 int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float* m0, float* wrow, float* ucol,
-              float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, hipStream_t s) {
+              float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, float* csum, hipStream_t s) {
     GateArgs g;
     g.i_pre = i_pre; g.f_pre = f_pre; g.m0 = d.variant == TFLA_EXP ? m0 : nullptr;
     g.T = d.T; g.L = d.L; g.Nc = d.Nc; g.variant = d.variant;
     g.qscale = 1.0f / sqrtf((float)d.dqk);
-    g.wrow = wrow; g.ucol = ucol; g.sH = sH; g.aK = aK; g.gbar = gbar; g.mout = mout; g.mfinal = mfinal; g.tmp = tmp;
+    g.wrow = wrow; g.ucol = ucol; g.sH = sH; g.aK = aK; g.gbar = gbar; g.mout = mout; g.mfinal = mfinal; g.tmp = tmp; g.csum = csum;
     TFLA_LAUNCH(K_GATES, launch_gates(g, (int)d.BH, s));
     return TFLA_OK;
 }
@@ -256,7 +260,7 @@ int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_p
 
     // 1. gates, max states
     float* mout = (is_exp && m_out) ? m_out : w.mout;
-    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, s);
+    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, s);
     if (st != TFLA_OK) return st;
 
     // 2. recurrent kernel: C_{k-1} (transposed, element type of q/k/v) and n_{k-1} for every chunk
@@ -327,7 +331,7 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
 
     // 1. gates as in the forward pass, then fold 1/h_denom into the backward weights
     if (!reuse) {
-        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, s);
+        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, s);
         if (st != TFLA_OK) return st;
     }
     GateBwdPrepArgs p;
@@ -378,7 +382,7 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     GateGradArgs gg;
     gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
     gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
-    gg.BHT = d.BHT;
+    gg.BHT = d.BHT; gg.bsum = w.bsum;
     TFLA_LAUNCH(K_GATE_GRADS, launch_gate_grads(gg, (int)d.BH, s));
     return TFLA_OK;
 }

@@ -36,105 +36,150 @@ __device__ __forceinline__ float wave_excl_scan_max(float v, int lane) {
     return lane == 0 ? -INFINITY : p;
 }
 
-// One workgroup per (batch, head).  Phase 1: every wave takes chunks round-robin and forms,
-// for chunk k: b = cumsum(f-bar), a = reverse cumsum shifted by one + i-bar (the stable form of
-// App. B.2), the running maximum of (i-bar_j - b_j), g_k = sum f-bar and max_j a_j.
-// Phase 2: one thread runs the scalar recurrence m_k = max(g_k + m_{k-1}, max_j a_kj).
-// Phase 3: the per-step quantities the matrix kernels consume.
+// The gate pre-pass runs as two kernels, each with one wavefront per chunk (four chunks per
+// workgroup), so that it fills the chip also when batch * heads is small.
+//
+// Kernel 1, for chunk k: b = cumsum(f-bar), a = reverse cumsum shifted by one + i-bar (the stable
+// form of App. B.2), the running maximum of (i-bar_j - b_j), and the chunk summaries g_k = sum
+// f-bar and max_j a_j.
+// Kernel 2: every workgroup first runs the scalar recurrence m_k = max(g_k + m_{k-1}, max_j a_kj)
+// over all chunks of its (batch, head) -- as a scan: the maps m -> max(m + g, c) compose to
+// (g1 + g2, max(c1 + g2, c2)) -- and then forms the per-step quantities the matrix kernels
+// consume for its own chunks.
 //
 // The intra-chunk row maximum is separable: max_{j<=i}(b_i - b_j + i-bar_j) = b_i +
 // cummax_j(i-bar_j - b_j), so the combined max state m_i = b_i + max(m_{k-1}, cummax_i) is known
 // before any matrix product and no online rescaling is needed in the tiled kernel.
-__global__ void __launch_bounds__(1024) gates_kernel(GateArgs a) {
-    extern __shared__ float sm[];
-    float* cg = sm;                 // [Nc]
-    float* camax = sm + a.Nc;       // [Nc]
-    float* cm = sm + 2 * a.Nc;      // [Nc + 1]
-    const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+static constexpr int GATE_WAVES = 4;
+
+__global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a) {
+    const int bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int kc = blockIdx.x * GATE_WAVES + wave;
+    if (kc >= a.Nc) return;
     const int E = a.L / 64;
     const bool is_exp = a.variant == 0;
     const long row = (long)bh * a.T;
     float* tb = a.tmp + (long)bh * 3 * a.T;
     float* tc = tb + a.T;
     float* ta = tc + a.T;
+    const long t0 = (long)kc * a.L + (long)lane * E;
+    float fsum = 0.0f;
+    for (int e = 0; e < E; ++e) fsum += log_sigmoid(a.f_pre[row + t0 + e]);
+    const float off = wave_excl_scan_add(fsum, lane);
+    const float roff = wave_excl_rscan_add(fsum, lane);
+    // forward pass: b, u = i-bar - b, running max of u
+    float b = off, cmx = -INFINITY;
+    for (int e = 0; e < E; ++e) {
+        const float fb = log_sigmoid(a.f_pre[row + t0 + e]);
+        const float ip = a.i_pre[row + t0 + e];
+        const float ib = is_exp ? ip : log_sigmoid(ip);
+        b += fb;
+        cmx = fmaxf(cmx, ib - b);
+    }
+    const float cmoff = wave_excl_scan_max(cmx, lane);
+    b = off; cmx = cmoff;
+    for (int e = 0; e < E; ++e) {
+        const float fb = log_sigmoid(a.f_pre[row + t0 + e]);
+        const float ip = a.i_pre[row + t0 + e];
+        const float ib = is_exp ? ip : log_sigmoid(ip);
+        b += fb;
+        const float u = ib - b;
+        cmx = fmaxf(cmx, u);
+        tb[t0 + e] = b;
+        tc[t0 + e] = cmx;
+        a.ucol[row + t0 + e] = u * LOG2E;
+    }
+    // reverse pass: a_j = sum_{s>j} f-bar_s + i-bar_j
+    float run = roff, amax = -INFINITY;
+    for (int e = E - 1; e >= 0; --e) {
+        const float ip = a.i_pre[row + t0 + e];
+        const float ib = is_exp ? ip : log_sigmoid(ip);
+        const float av = run + ib;
+        ta[t0 + e] = av;
+        amax = fmaxf(amax, av);
+        run += log_sigmoid(a.f_pre[row + t0 + e]);
+    }
+    amax = wave_max(amax);
+    const float gsum = wave_sum(fsum);
+    if (lane == 0) {
+        a.csum[((long)bh * 2 + 0) * a.Nc + kc] = gsum;
+        a.csum[((long)bh * 2 + 1) * a.Nc + kc] = amax;
+    }
+}
 
-    for (int kc = wave; kc < a.Nc; kc += nw) {
-        const long t0 = (long)kc * a.L + (long)lane * E;
-        float fsum = 0.0f;
-        for (int e = 0; e < E; ++e) fsum += log_sigmoid(a.f_pre[row + t0 + e]);
-        const float off = wave_excl_scan_add(fsum, lane);
-        const float roff = wave_excl_rscan_add(fsum, lane);
-        // forward pass: b, u = i-bar - b, running max of u
-        float b = off, cmx = -INFINITY;
-        for (int e = 0; e < E; ++e) {
-            const float fb = log_sigmoid(a.f_pre[row + t0 + e]);
-            const float ip = a.i_pre[row + t0 + e];
-            const float ib = is_exp ? ip : log_sigmoid(ip);
-            b += fb;
-            const float u = ib - b;
-            cmx = fmaxf(cmx, u);
-            tb[t0 + e] = b;
-            tc[t0 + e] = cmx;
-            a.ucol[row + t0 + e] = u * LOG2E;
+__global__ void __launch_bounds__(GATE_WAVES * 64) gates_step_kernel(GateArgs a) {
+    extern __shared__ float cm[];   // [Nc + 1]: m before chunk k
+    const int bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool is_exp = a.variant == 0;
+    const float* cg = a.csum + ((long)bh * 2 + 0) * a.Nc;
+    const float* camax = a.csum + ((long)bh * 2 + 1) * a.Nc;
+    if (wave == 0) {
+        // lane l composes the maps of its segment of chunks, a wavefront scan composes the segments,
+        // then every lane walks its segment again from its incoming m
+        const int seg = (a.Nc + 63) / 64;
+        const int k0 = lane * seg, k1 = min(a.Nc, k0 + seg);
+        float G = 0.0f, C = -INFINITY;
+        for (int k = k0; k < k1; ++k) { C = fmaxf(C + cg[k], camax[k]); G += cg[k]; }
+        // inclusive scan of the composed maps over the lanes
+        float Gs = G, Cs = C;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const float Gp = __shfl_up(Gs, o, 64), Cp = __shfl_up(Cs, o, 64);
+            if (lane >= o) { Cs = fmaxf(Cp + Gs, Cs); Gs = Gp + Gs; }
         }
-        const float cmoff = wave_excl_scan_max(cmx, lane);
-        for (int e = 0; e < E; ++e) tc[t0 + e] = fmaxf(tc[t0 + e], cmoff);
-        // reverse pass: a_j = sum_{s>j} f-bar_s + i-bar_j
-        float run = roff, amax = -INFINITY;
-        for (int e = E - 1; e >= 0; --e) {
-            const float ip = a.i_pre[row + t0 + e];
-            const float ib = is_exp ? ip : log_sigmoid(ip);
-            const float av = run + ib;
-            ta[t0 + e] = av;
-            amax = fmaxf(amax, av);
-            run += log_sigmoid(a.f_pre[row + t0 + e]);
-        }
-        amax = wave_max(amax);
-        const float g = wave_sum(fsum);
-        if (lane == 0) { cg[kc] = g; camax[kc] = amax; }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        float m = (is_exp && a.m0) ? a.m0[bh] : 0.0f;
-        cm[0] = m;
-        for (int kc = 0; kc < a.Nc; ++kc) {
-            const float mn = is_exp ? fmaxf(cg[kc] + m, camax[kc]) : 0.0f;
-            a.gbar[(long)bh * a.Nc + kc] = expf(cg[kc] + m - mn);
+        // exclusive: the map of all chunks before this lane's segment, applied to m0
+        const float Ge = __shfl_up(Gs, 1, 64), Ce = __shfl_up(Cs, 1, 64);
+        const float m_init = (is_exp && a.m0) ? a.m0[bh] : 0.0f;
+        float m = lane == 0 ? m_init : fmaxf(m_init + Ge, Ce);
+        if (!is_exp) m = 0.0f;
+        for (int k = k0; k < k1; ++k) {
+            cm[k] = m;
+            const float mn = is_exp ? fmaxf(cg[k] + m, camax[k]) : 0.0f;
+            if (blockIdx.x == 0) a.gbar[(long)bh * a.Nc + k] = expf(cg[k] + m - mn);
             m = mn;
-            cm[kc + 1] = m;
         }
-        if (a.mfinal) a.mfinal[bh] = m;
+        if (k1 == a.Nc && k0 < k1) {
+            cm[a.Nc] = m;
+            if (blockIdx.x == 0 && a.mfinal) a.mfinal[bh] = m;
+        }
     }
     __syncthreads();
+    const int kc = blockIdx.x * GATE_WAVES + wave;
+    if (kc >= a.Nc) return;
+    const int E = a.L / 64;
+    const long row = (long)bh * a.T;
+    const float* tb = a.tmp + (long)bh * 3 * a.T;
+    const float* tc = tb + a.T;
+    const float* ta = tc + a.T;
     const float lq = log2f(a.qscale);
-    for (int kc = wave; kc < a.Nc; kc += nw) {
-        const long t0 = (long)kc * a.L + (long)lane * E;
-        const float mprev = cm[kc], mk = cm[kc + 1];
-        for (int e = 0; e < E; ++e) {
-            const float b = tb[t0 + e], cmx = tc[t0 + e], av = ta[t0 + e];
-            float wr, sh, mo;
-            if (is_exp) {
-                const float M = fmaxf(mprev, cmx);
-                wr = -M * LOG2E + lq;
-                sh = expf(mprev - M) * a.qscale;
-                mo = b + M;
-            } else {
-                wr = b * LOG2E + lq;
-                sh = expf(b) * a.qscale;
-                mo = 0.0f;
-            }
-            a.wrow[row + t0 + e] = wr;
-            a.sH[row + t0 + e] = sh;
-            a.aK[row + t0 + e] = expf(av - mk);
-            a.mout[row + t0 + e] = mo;
+    const long t0 = (long)kc * a.L + (long)lane * E;
+    const float mprev = cm[kc], mk = cm[kc + 1];
+    for (int e = 0; e < E; ++e) {
+        const float b = tb[t0 + e], cmx = tc[t0 + e], av = ta[t0 + e];
+        float wr, sh, mo;
+        if (is_exp) {
+            const float M = fmaxf(mprev, cmx);
+            wr = -M * LOG2E + lq;
+            sh = expf(mprev - M) * a.qscale;
+            mo = b + M;
+        } else {
+            wr = b * LOG2E + lq;
+            sh = expf(b) * a.qscale;
+            mo = 0.0f;
         }
+        a.wrow[row + t0 + e] = wr;
+        a.sH[row + t0 + e] = sh;
+        a.aK[row + t0 + e] = expf(av - mk);
+        a.mout[row + t0 + e] = mo;
     }
 }
 
 hipError_t launch_gates(const GateArgs& a, int BH, hipStream_t s) {
-    const size_t sh = sizeof(float) * (size_t)(3 * a.Nc + 1);
-    const int nt = a.Nc >= 16 ? 1024 : (a.Nc >= 4 ? 256 : 64);
-    hipLaunchKernelGGL(gates_kernel, dim3(BH), dim3(nt), sh, s, a);
+    const dim3 grid((a.Nc + GATE_WAVES - 1) / GATE_WAVES, BH);
+    hipLaunchKernelGGL(gates_chunk_kernel, grid, dim3(GATE_WAVES * 64), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(gates_step_kernel, grid, dim3(GATE_WAVES * 64), sizeof(float) * (size_t)(a.Nc + 1), s, a);
     return hipGetLastError();
 }
 
@@ -158,45 +203,88 @@ hipError_t launch_gate_bwd_prep(const GateBwdPrepArgs& a, hipStream_t s) {
 //   d i-bar_j = k_j . dk_j ,   d f-bar_s = sum_{t>=s} (q_t . dq_t - k_t . dk_t) + <C_T, dC_T>.
 // This regroups the cumulative-gate gradients of App. B.3 (delta g, delta a, delta b and the
 // row/column sums of the intra-chunk gate-matrix gradient) into one reverse cumulative sum.
-__global__ void __launch_bounds__(1024) gate_grads_kernel(GateGradArgs a) {
-    __shared__ double wt[16];
-    const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int seg = (a.T + 1023) / 1024;
+// Two kernels over blocks of GG_BLOCK steps: block sums first, then every block adds the sums of
+// the blocks after it and scans its own steps (in fp64: the terms cancel heavily).
+static constexpr int GG_BLOCK = 1024;
+
+__device__ __forceinline__ void gate_grad_terms(const GateGradArgs& a, long idx, float& r, float& c) {
+    r = 0.0f; c = 0.0f;
+    for (int nb = 0; nb < a.nbQ; ++nb) r += a.partQ[(long)nb * a.BHT + idx];
+    for (int nb = 0; nb < a.nbK; ++nb) c += a.partK[(long)nb * a.BHT + idx];
+}
+
+__global__ void __launch_bounds__(256) gate_grads_sum_kernel(GateGradArgs a) {
+    __shared__ double wt[4];
+    const int bh = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
     const long row = (long)bh * a.T;
-    const int t0 = tid * seg;
     double tot = 0.0;
-    for (int e = 0; e < seg; ++e) {
-        const int t = t0 + e;
+    for (int e = 0; e < GG_BLOCK / 256; ++e) {
+        const int t = blk * GG_BLOCK + e * 256 + tid;
         if (t < a.T) {
-            float r = 0.0f, c = 0.0f;
-            for (int nb = 0; nb < a.nbQ; ++nb) r += a.partQ[(long)nb * a.BHT + row + t];
-            for (int nb = 0; nb < a.nbK; ++nb) c += a.partK[(long)nb * a.BHT + row + t];
+            float r, c;
+            gate_grad_terms(a, row + t, r, c);
             tot += (double)r - (double)c;
         }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o, 64);
+    if ((tid & 63) == 0) wt[tid >> 6] = tot;
+    __syncthreads();
+    if (tid == 0) a.bsum[(long)bh * gridDim.x + blk] = wt[0] + wt[1] + wt[2] + wt[3];
+}
+
+__global__ void __launch_bounds__(256) gate_grads_kernel(GateGradArgs a) {
+    __shared__ double wt[4];
+    __shared__ double after;
+    const int bh = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nblk = gridDim.x;
+    const long row = (long)bh * a.T;
+    // sum of the blocks after this one
+    double later = 0.0;
+    for (int b2 = blk + 1 + tid; b2 < nblk; b2 += 256) later += a.bsum[(long)bh * nblk + b2];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) later += __shfl_xor(later, o, 64);
+    if (lane == 0) wt[wave] = later;
+    __syncthreads();
+    if (tid == 0) after = wt[0] + wt[1] + wt[2] + wt[3] + (a.cdot ? (double)a.cdot[bh] : 0.0);
+    __syncthreads();
+    // thread tid owns GG_BLOCK / 256 consecutive steps
+    constexpr int SEG = GG_BLOCK / 256;
+    const int t0 = blk * GG_BLOCK + tid * SEG;
+    float r[SEG], c[SEG];
+    double tot = 0.0;
+#pragma unroll
+    for (int e = 0; e < SEG; ++e) {
+        r[e] = 0.0f; c[e] = 0.0f;
+        if (t0 + e < a.T) gate_grad_terms(a, row + t0 + e, r[e], c[e]);
+        tot += (double)r[e] - (double)c[e];
     }
     double x = tot;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) { const double y = __shfl_down(x, o, 64); if (lane + o < 64) x += y; }
     double excl = __shfl_down(x, 1, 64);
     if (lane == 63) excl = 0.0;
+    __syncthreads();
     if (lane == 0) wt[wave] = x;
     __syncthreads();
-    for (int w = wave + 1; w < 16; ++w) excl += wt[w];
-    double run = excl + (a.cdot ? (double)a.cdot[bh] : 0.0);
-    for (int e = seg - 1; e >= 0; --e) {
+    for (int w = wave + 1; w < 4; ++w) excl += wt[w];
+    double run = excl + after;
+#pragma unroll
+    for (int e = SEG - 1; e >= 0; --e) {
         const int t = t0 + e;
         if (t < a.T) {
-            float r = 0.0f, c = 0.0f;
-            for (int nb = 0; nb < a.nbQ; ++nb) r += a.partQ[(long)nb * a.BHT + row + t];
-            for (int nb = 0; nb < a.nbK; ++nb) c += a.partK[(long)nb * a.BHT + row + t];
-            run += (double)r - (double)c;
+            run += (double)r[e] - (double)c[e];
             a.d_f[row + t] = (float)run * sigmoid_neg(a.f_pre[row + t]);
-            a.d_i[row + t] = a.variant == 0 ? c : c * sigmoid_neg(a.i_pre[row + t]);
+            a.d_i[row + t] = a.variant == 0 ? c[e] : c[e] * sigmoid_neg(a.i_pre[row + t]);
         }
     }
 }
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s) {
-    hipLaunchKernelGGL(gate_grads_kernel, dim3(BH), dim3(1024), 0, s, a);
+    const dim3 grid((a.T + GG_BLOCK - 1) / GG_BLOCK, BH);
+    hipLaunchKernelGGL(gate_grads_sum_kernel, grid, dim3(256), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(gate_grads_kernel, grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

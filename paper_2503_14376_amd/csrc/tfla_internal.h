@@ -22,6 +22,7 @@ struct GateArgs {
     float* mout;          // combined max state m_t of every step
     float* mfinal;        // (BH) m after the last chunk, or NULL
     float* tmp;           // (BH, 3, T) scratch
+    float* csum;          // (BH, 2, Nc) scratch: per-chunk sum of f-bar and max of a
 };
 hipError_t launch_gates(const GateArgs& a, int BH, hipStream_t s);
 
@@ -38,6 +39,7 @@ struct GateGradArgs {
     const float* cdot;             // (BH) <C_T, dC_T> or NULL
     const float* i_pre; const float* f_pre;
     float* d_i; float* d_f;
+    double* bsum;                  // (BH, ceil(T / 1024)) scratch: block sums
     int T, variant; long BHT;
 };
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
