@@ -35,9 +35,9 @@ namespace tfla {
 // development aid: phase timestamps of the first consumer and the first producer of workgroup 0,
 // kept in LDS during the run (a global store would disturb the load counters being studied)
 static __device__ unsigned long long tfla_rec_timeline[8192];
-#define TFLA_RTL_DECL __shared__ unsigned long long tl_lds[2][512];
-#define TFLA_RTL(slot) if ((tid & 255) == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && (slot) >= 0 && (slot) < 512) tl_lds[tid >> 8][(slot)] = __builtin_amdgcn_s_memtime()
-#define TFLA_RTL_FLUSH __syncthreads(); if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) for (int q_ = tid; q_ < 1024; q_ += blockDim.x) tfla_rec_timeline[(q_ >> 9) * 4096 + (q_ & 511)] = tl_lds[q_ >> 9][q_ & 511];
+#define TFLA_RTL_DECL __shared__ unsigned long long tl_lds[2][128];
+#define TFLA_RTL(slot) if ((tid & 255) == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && (slot) >= 0 && (slot) < 128) tl_lds[tid >> 8][(slot)] = __builtin_amdgcn_s_memtime()
+#define TFLA_RTL_FLUSH __syncthreads(); if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) for (int q_ = tid; q_ < 256; q_ += blockDim.x) tfla_rec_timeline[(q_ >> 7) * 4096 + (q_ & 127)] = tl_lds[q_ >> 7][q_ & 127];
 #else
 #define TFLA_RTL_DECL
 #define TFLA_RTL(slot)

@@ -42,6 +42,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     constexpr int BCS_RAW = STAGE / (BD2 * 2);
     constexpr int BCS = BCS_RAW >= D1 ? D1 : (BCS_RAW >= 64 ? 64 : 32);             // state slice width
     constexpr int NKS = D1 / BCS;
+    // the workgroup's rows of X arrive in [BR][BXS] slices
+    constexpr int BXS_RAW = STAGE / (BR * 2);
+    constexpr int BXS = BXS_RAW >= 128 ? 128 : (BXS_RAW >= 64 ? 64 : 32);
+    constexpr int NXS = D1 / BXS, NPRE = NXS + NKS;
+    static_assert(BR * BXS * 2 <= STAGE && BXS <= D1 && D1 % BXS == 0, "X slice must fit a stage");
     static_assert(BD2 * BCS * 2 <= STAGE && BCS <= 64 && D1 % BCS == 0, "state slice must fit a stage");
 
     // after the loops the ring's memory holds the output block (and the dot operand) of each wave
@@ -78,23 +83,29 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 
     const int ct_lo = UPPER ? r0 / BC : 0;
     const int ct_hi = UPPER ? a.L / BC : (r0 + BR) / BC;
-    const int NI = NKS + (ct_hi - ct_lo);                       // items streamed through the ring
+    const int NI = NPRE + (ct_hi - ct_lo);                      // items streamed through the ring
 
     using DS = typename std::conditional<STT, DmaTile<BCS, BD2, NT, SWZ_T>, DmaTile<BD2, BCS, NT, SWZ_K>>::type;
     DS ds;  ds.init(STT ? d2 : D1, tid);
     DmaTile<BC, D1, NT, SWZ_K> dy;    dy.init(D1, tid);
     DmaTile<BC, BD2, NT, SWZ_T> dz;   dz.init(d2, tid);
     constexpr int CS = DS::N;
+    DmaTile<BR, BXS, NT, SWZ_K> dxs;  dxs.init(D1, tid);
+    constexpr int CX = DmaTile<BR, BXS, NT, SWZ_K>::N;
+    const bf16_t* Xb = X + (tbase + r0) * D1;
     constexpr int CT = DmaTile<BC, D1, NT, SWZ_K>::N + DmaTile<BC, BD2, NT, SWZ_T>::N + 1;
     const uint32_t smem_a = lds_addr(smem), w_a = lds_addr(ldsW);
     const float* wcol = a.wcol + tbase;
 
     auto issue = [&](int item) {
         const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
-        if (item < NKS) {
-            ds.issue(St + (STT ? (long)item * BCS * d2 : (long)item * BCS), st, tid);
+        if (item < NXS) {
+            dxs.issue(Xb + item * BXS, st, tid);
+        } else if (item < NPRE) {
+            const int sl = item - NXS;
+            ds.issue(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid);
         } else {
-            const int ct = ct_lo + item - NKS;
+            const int ct = ct_lo + item - NPRE;
             dy.issue(Y + (long)ct * BC * D1, st, tid);
             dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
             // the tile's 32 column weights (both half-waves fetch the same 32 floats)
@@ -106,18 +117,12 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         int p = 0;
 #pragma unroll
         for (int j = 1; j <= NS - 2; ++j)
-            if (i + j < NI) p += (i + j < NKS) ? CS : CT;
+            if (i + j < NI) p += (i + j < NXS) ? CX : ((i + j < NPRE) ? CS : CT);
         return p;
     };
 
-    // X fragments of the wavefront's 32 rows (lane: row l32, k-group g), straight from global, and
-    // the per-row scalars of the workgroup's rows; issued before the ring so they return first
-    frag xf[KS1];
-    {
-        const bf16_t* xr = X + (tbase + wr0 + l32) * D1 + 8 * g;
-#pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) xf[ks] = E::load(xr + 16 * ks);
-    }
+    // per-row scalars of the workgroup's rows, issued before the ring so that, loads retiring in
+    // order, they have landed once the first ring item has
     {
         const uint32_t vo = (uint32_t)(lane & 31) * 4u;
         dma4(a.srow + tbase + wr0, vo, lds_addr(&ldsS[wave][0]));
@@ -133,10 +138,24 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
     for (int p = 0; p < NS - 1; ++p)
         if (p < NI) issue(p);
-    // everything above must have landed before the ring's wait counts are relied upon
-    wait_vmcnt<0>();
-    __syncthreads();
     TFLA_TL(1);
+
+    // ---------------- X fragments of the wavefront's 32 rows (lane: row l32, k-group g)
+    frag xf[KS1];
+    {
+        KFragReader<BXS> rx;  rx.init(l32, g);
+#pragma unroll
+        for (int i = 0; i < NXS; ++i) {
+            wait_vmcnt_dyn(pending_after(i));
+            // the fragment reads of the previous slice have left LDS before its stage is refilled
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            barrier_nofence();
+            if (i + NS - 1 < NI) issue(i + NS - 1);
+            const char* sb = smem + (i % NS) * STAGE;
+#pragma unroll
+            for (int ks = 0; ks < BXS / 16; ++ks) xf[i * (BXS / 16) + ks].v = rx.load(sb, ks, wave);
+        }
+    }
 
     KFragReader<BCS> rs_;  rs_.init(l32, g);
     KFragReader<D1> ry;    ry.init(l32, g);
@@ -152,10 +171,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     // ---------------- inter-chunk part: acc = X_r St
 #pragma unroll
     for (int i = 0; i < NKS; ++i) {
-        wait_vmcnt_dyn(pending_after(i));
+        wait_vmcnt_dyn(pending_after(NXS + i));
+        if (i == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         barrier_nofence();
-        if (i + NS - 1 < NI) issue(i + NS - 1);
-        const char* sb = smem + (i % NS) * STAGE;
+        if (NXS + i + NS - 1 < NI) issue(NXS + i + NS - 1);
+        const char* sb = smem + ((NXS + i) % NS) * STAGE;
         {
             constexpr int NF = (BCS / 16) * NB;
             frag b[BCS / 16][NB];
@@ -206,7 +226,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     const float wr = ldsWr[wave][l32];
     float rowsum = 0.0f;
     for (int ct = ct_lo; ct < ct_hi; ++ct) {
-        const int i = NKS + ct - ct_lo;
+        const int i = NPRE + ct - ct_lo;
         wait_vmcnt_dyn(pending_after(i));
         barrier_nofence();
         if (i + NS - 1 < NI) issue(i + NS - 1);
