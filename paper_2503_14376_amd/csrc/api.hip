@@ -82,7 +82,7 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
 struct BwdWs {
     float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal;
     double* bsum;
-    void *cN, *dcT, *dcN;
+    void *cN, *dcT, *dcN, *E;
     int nbQ, nbK;
     size_t bytes;
 };
@@ -104,6 +104,8 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     // bf16: C_{k-1} and dC_k, both as (d_hv, d_qk); fp32 additionally dC_k as (d_qk, d_hv)
     w.cN = c.take_bytes(st); w.dcT = c.take_bytes(st);
     w.dcN = d.dtype == TFLA_BF16 ? nullptr : c.take_bytes(st);
+    // bf16: the weighted intra-chunk matrix shared by dQ and dK, (BH, Nc, L, L)
+    w.E = d.dtype == TFLA_BF16 ? c.take_bytes((size_t)d.BHT * d.L * d.esz) : nullptr;
     w.bytes = c.off;
     return w;
 }
@@ -277,7 +279,7 @@ int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_p
     t.wrow = w.wrow; t.wcol = w.ucol; t.srow = w.sH; t.St = w.stT;
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
     t.variant = variant; t.eps = eps; t.nstate = w.nst; t.mout = mout; t.nout = is_exp ? n_out : nullptr;
-    t.dotwith = nullptr; t.dotpart = nullptr;
+    t.dotwith = nullptr; t.dotpart = nullptr; t.E = nullptr;
     TFLA_LAUNCH(K_TILE_H, launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
 
     if (!is_exp) {
@@ -363,7 +365,7 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     // 4. the three gradient kernels
     TileArgs t;
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
-    t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr;
+    t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr; t.E = w.E;
     // dV: rows = kv index j
     t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = w.dcT;
     t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;

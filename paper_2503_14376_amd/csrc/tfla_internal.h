@@ -85,6 +85,8 @@ struct TileArgs {
     // MODE_DQ / MODE_DK: partial row dots  sum_n out[r,n] * dotwith[r,n]
     const void* dotwith;            // (BH, T, d2)
     float* dotpart;                 // (d2/BD2, BH*T)
+    // bf16 MODE_DQ writes, bf16 MODE_DK reads: the weighted matrix E of every chunk, (BH, Nc, L, L)
+    void* E;
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
 // d2 block of a tiled kernel with contraction width d1.  bf16, d1 <= 256: 128 columns, which keeps

@@ -32,15 +32,20 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     using frag = E::frag;
     constexpr bool UPPER = (MODE & 1) != 0;
     constexpr bool STT = (MODE == MODE_DQ || MODE == MODE_DK);   // state slices are contraction-major
+    constexpr bool ELITE = MODE == MODE_DK;                      // column tiles carry E instead of Y
+    constexpr bool EWRITE = MODE == MODE_DQ;
     constexpr int NT = NW * 64, BR = NW * 32, BC = 32;
     constexpr int KS1 = D1 / 16, NB = BD2 / 32;
-    constexpr int YB = BC * D1 * 2, ZB = BC * BD2 * 2, STAGE = YB + ZB;             // bytes
+    constexpr int YB = ELITE ? BC * BR * 2 : BC * D1 * 2, ZB = BC * BD2 * 2;         // bytes
+    constexpr int XSMIN = BR * (D1 < 128 ? D1 : 128) * 2;       // room for wide X slices when the tiles are small
+    constexpr int STAGE = (ELITE && YB + ZB < XSMIN) ? XSMIN : YB + ZB;
+    constexpr int ESTG = EWRITE ? NW * 2048 : 0;                // per-wave staging of E tiles
     // LDS budget of one workgroup: 160 KB shared by OCC resident workgroups, minus the small arrays
-    constexpr int BUDGET = (OCC >= 2 ? 80 : 160) * 1024 - 6144;
+    constexpr int BUDGET = (OCC >= 2 ? 80 : 160) * 1024 - 6144 - ESTG;
     constexpr int NS = STAGE * 4 <= BUDGET ? 4 : (STAGE * 3 <= BUDGET ? 3 : 2);
     static_assert(NS * STAGE <= BUDGET, "ring does not fit");
     constexpr int BCS_RAW = STAGE / (BD2 * 2);
-    constexpr int BCS = BCS_RAW >= D1 ? D1 : (BCS_RAW >= 64 ? 64 : 32);             // state slice width
+    constexpr int BCS = BCS_RAW >= 64 ? 64 : 32;                                    // state slice width
     constexpr int NKS = D1 / BCS;
     // the workgroup's rows of X arrive in [BR][BXS] slices
     constexpr int BXS_RAW = STAGE / (BR * 2);
@@ -54,6 +59,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     constexpr int SMEM = NS * STAGE > EPI ? NS * STAGE : EPI;
     static_assert(SMEM <= BUDGET, "LDS budget");
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
+    __shared__ __attribute__((aligned(1024))) char ldsE[EWRITE ? ESTG : 16];
     __shared__ __attribute__((aligned(256))) float ldsW[NS][NW][64];   // column weights of a tile, one copy per wave
     // per-row scalars of each wave's 32 rows (two copies side by side), fetched like the tiles
     __shared__ __attribute__((aligned(256))) float ldsS[NW][64];    // inter-chunk row scale
@@ -87,13 +93,16 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 
     using DS = typename std::conditional<STT, DmaTile<BCS, BD2, NT, SWZ_T>, DmaTile<BD2, BCS, NT, SWZ_K>>::type;
     DS ds;  ds.init(STT ? d2 : D1, tid);
-    DmaTile<BC, D1, NT, SWZ_K> dy;    dy.init(D1, tid);
+    using DYT = typename std::conditional<ELITE, DmaTile<BC, BR, NT, SWZ_T>, DmaTile<BC, D1, NT, SWZ_K>>::type;
+    DYT dy;    dy.init(ELITE ? a.L : D1, tid);
     DmaTile<BC, BD2, NT, SWZ_T> dz;   dz.init(d2, tid);
+    // E of this chunk: (L, L), rows = query index; the dK kernel reads the columns of its own rows
+    const bf16_t* Eb = reinterpret_cast<const bf16_t*>(a.E) + ((long)bh * a.Nc + kc) * a.L * a.L + (ELITE ? r0 : 0);
     constexpr int CS = DS::N;
     DmaTile<BR, BXS, NT, SWZ_K> dxs;  dxs.init(D1, tid);
     constexpr int CX = DmaTile<BR, BXS, NT, SWZ_K>::N;
     const bf16_t* Xb = X + (tbase + r0) * D1;
-    constexpr int CT = DmaTile<BC, D1, NT, SWZ_K>::N + DmaTile<BC, BD2, NT, SWZ_T>::N + 1;
+    constexpr int CT = DYT::N + DmaTile<BC, BD2, NT, SWZ_T>::N + (ELITE ? 0 : 1);
     const uint32_t smem_a = lds_addr(smem), w_a = lds_addr(ldsW);
     const float* wcol = a.wcol + tbase;
 
@@ -106,10 +115,15 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             ds.issue(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid);
         } else {
             const int ct = ct_lo + item - NPRE;
-            dy.issue(Y + (long)ct * BC * D1, st, tid);
-            dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
-            // the tile's 32 column weights (both half-waves fetch the same 32 floats)
-            dma4(wcol + ct * BC, (uint32_t)(lane & 31) * 4u, w_a + (uint32_t)(((item % NS) * NW + wave) * 256));
+            if (ELITE) {
+                dy.issue(Eb + (long)ct * BC * a.L, st, tid);
+                dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
+            } else {
+                dy.issue(Y + (long)ct * BC * D1, st, tid);
+                dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
+                // the tile's 32 column weights (both half-waves fetch the same 32 floats)
+                dma4(wcol + ct * BC, (uint32_t)(lane & 31) * 4u, w_a + (uint32_t)(((item % NS) * NW + wave) * 256));
+            }
         }
     };
     // loads of this wave issued after those of item i and still allowed in flight while waiting for i
@@ -225,6 +239,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     // ---------------- intra-chunk part, one 32-column tile per item
     const float wr = ldsWr[wave][l32];
     float rowsum = 0.0f;
+    uint32_t eoff = 0;
+    if constexpr (ELITE) {
+        TFragReader<BR> re;  re.init(lane, 4);
+        eoff = re.block_offset(wave);
+    }
     for (int ct = ct_lo; ct < ct_hi; ++ct) {
         const int i = NPRE + ct - ct_lo;
         wait_vmcnt_dyn(pending_after(i));
@@ -236,6 +255,12 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         const char* yb = smem + (i % NS) * STAGE;
         const char* zb = yb + YB;
         const float* wb = &ldsW[i % NS][wave][0];
+        frag p0, p1;
+        if constexpr (ELITE) {
+            // E^T of this wave's rows: the tile is [32 query rows][BR rows of this workgroup]
+            p0.v = TFragReader<BR>::load_at(yb, eoff, 0, 8);
+            p1.v = TFragReader<BR>::load_at(yb, eoff, 16, 24);
+        } else {
         f32x16 s;
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.0f;
@@ -274,7 +299,29 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) rowsum += p[v];
         }
-        const frag p0 = E::pack(p), p1 = E::pack(p + 8);
+        p0 = E::pack(p); p1 = E::pack(p + 8);
+        if constexpr (EWRITE) {
+            if (nb2 == 0 && a.E) {
+                // E[wr0 + r][cs + c]: through a wave-private [32 r][32 c] tile so that rows leave in
+                // 64-byte segments; lane (r, g) holds c = 8 q + 4 g + {0..3} in register pair q
+                char* et = ldsE + wave * 2048;
+                const u32x4 w0 = __builtin_bit_cast(u32x4, p0.v), w1 = __builtin_bit_cast(u32x4, p1.v);
+                const int sw = (l32 >> 1) & 3;
+                *reinterpret_cast<uint2*>(et + l32 * 64 + ((0 ^ sw) * 16) + 8 * g) = uint2{w0[0], w0[1]};
+                *reinterpret_cast<uint2*>(et + l32 * 64 + ((1 ^ sw) * 16) + 8 * g) = uint2{w0[2], w0[3]};
+                *reinterpret_cast<uint2*>(et + l32 * 64 + ((2 ^ sw) * 16) + 8 * g) = uint2{w1[0], w1[1]};
+                *reinterpret_cast<uint2*>(et + l32 * 64 + ((3 ^ sw) * 16) + 8 * g) = uint2{w1[2], w1[3]};
+                char* eg = reinterpret_cast<char*>(a.E) +
+                           ((((long)bh * a.Nc + kc) * a.L + wr0) * a.L + cs) * 2;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int n = q * 16 + (lane >> 2), c4 = lane & 3;
+                    const u32x4 w = *reinterpret_cast<const u32x4*>(et + n * 64 + ((c4 ^ ((n >> 1) & 3)) * 16));
+                    *reinterpret_cast<u32x4*>(eg + ((long)n * a.L + 8 * c4) * 2) = w;
+                }
+            }
+        }
+        }
         {
             frag z[NB][2];
 #pragma unroll
