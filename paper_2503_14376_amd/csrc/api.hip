@@ -95,8 +95,8 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.csum = c.take<float>(2 * d.BH * d.Nc);
     w.bsum = c.take<double>(d.BH * ((d.T + 1023) / 1024));
     w.wrowB = c.take<float>(d.BHT); w.sQ = c.take<float>(d.BHT);
-    w.nbQ = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype);
-    w.nbK = w.nbQ;
+    w.nbQ = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DQ);
+    w.nbK = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DK);
     w.partQ = c.take<float>((size_t)w.nbQ * d.BHT); w.partK = c.take<float>((size_t)w.nbK * d.BHT);
     w.cdot = c.take<float>(d.BH);
     w.Cfinal = c.take<float>((size_t)d.BH * d.dqk * d.dhv);

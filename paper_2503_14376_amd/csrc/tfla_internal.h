@@ -89,11 +89,12 @@ struct TileArgs {
     void* E;
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
-// d2 block of a tiled kernel with contraction width d1.  bf16, d1 <= 256: 128 columns, which keeps
-// a wavefront within 256 registers so that two workgroups share a CU (one hides the other's
-// prologue, epilogue and barriers); bf16, d1 = 512: the X fragments alone take 128 registers, so one
-// workgroup per CU with a 256-wide block; fp32: what the generic kernel's register budget allows.
-inline int tile_bd2(int d1, int d2, int dtype) {
+// d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16
+// wavefront within 256 registers, so that two workgroups share a CU when d1 <= 256.  The bf16 dK
+// kernel, which computes no S of its own, takes a 256-wide block when d1 = 512 (one workgroup per
+// CU anyway): half as many workgroups fetch the same X rows and E tiles.
+inline int tile_bd2(int d1, int d2, int dtype, int mode) {
+    if (dtype == 1 && mode == MODE_DK && d1 == 512 && d2 % 256 == 0) return 256;
     if (d2 % 128 == 0) return 128;
     return 64;
 }

@@ -285,7 +285,7 @@ static hipError_t launch_tile_m(const TileArgs& a, int BH, int bd2, hipStream_t 
 
 template <int MODE>
 hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s) {
-    const int bd2 = tile_bd2(a.d1, a.d2, dtype);
+    const int bd2 = tile_bd2(a.d1, a.d2, dtype, MODE);
     return dtype == 1 ? launch_tile_m<bf16_t, MODE>(a, BH, bd2, s) : launch_tile_m<float, MODE>(a, BH, bd2, s);
 }
 
