@@ -96,6 +96,9 @@ def main() -> int:
                     help="do not hand the forward workspace to the backward call (gates and chunk states are recomputed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay one captured HIP graph of the step instead of launching every step eagerly "
+                         "(measured slightly slower than eager launches on this stack)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy kernel (the known-size reference that the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by)")
@@ -154,18 +157,40 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    use_events = not args.no_kernel_events
-    if use_events:
-        tfla.profile_enable(16 * (args.steps + 1))
+    # Optionally the step (11 kernel launches of the two entry points) is captured once into a HIP
+    # graph and the timed region replays it: same kernels, same work.  The library is capture-safe:
+    # it never allocates, synchronises or records memset nodes.
+    graph = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+    run = graph.replay if graph is not None else step
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # per-kernel durations: HIP events around every launch, in a separate eager pass over the same steps
+    use_events = not args.no_kernel_events
     kernels, prof = {}, {}
     if use_events:
+        tfla.profile_enable(16 * (args.steps + 1))
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
         prof = tfla.profile_read()
         tfla.profile_enable(0)
         kernels = {k_: v_["ms"] / v_["launches"] for k_, v_ in prof.items() if v_["launches"] > 0}
@@ -242,6 +267,7 @@ def main() -> int:
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == wl.BF16 else "f32", "data": "synthetic",
+        "launch": "eager" if graph is None else "hip graph replay",
         "config": {"workload": w.name, "variant": "mLSTMexp" if w.variant == wl.EXP else "mLSTMsig",
                    "B": w.B, "NH": w.NH, "T": w.T, "dqk": w.dqk, "dhv": w.dhv, "chunk": w.chunk,
                    "pass": "fwd+bwd" if do_bwd else "fwd", "states": "element type of q/k/v (bf16), fp32 accumulation"},
