@@ -82,6 +82,77 @@ MEASURED_TRAFFIC_C4 = {
 }
 
 
+def step_bench(args) -> int:
+    """Generation: one recurrent step (tfla_mlstm_step) per launch at the 7B head shape, state resident in
+    HBM and updated in place.  A secondary line (`--workload step`); the default line is the training step."""
+    import torch
+    import paper_2503_14376_amd as tfla
+    tfla.load_library()
+    B, NH, dqk, dhv = (args.batch or 8), 8, 256, 512
+    variant = wl.SIG if args.variant == "sig" else wl.EXP
+    g = torch.Generator(device="cuda").manual_seed(1005)
+    bf = torch.bfloat16
+    q = torch.randn((B, NH, dqk), device="cuda", generator=g).to(bf)
+    k = torch.randn((B, NH, dqk), device="cuda", generator=g).to(bf)
+    v = torch.randn((B, NH, dhv), device="cuda", generator=g).to(bf)
+    ip = torch.randn((B, NH), device="cuda", generator=g)
+    fp = torch.randn((B, NH), device="cuda", generator=g) + 3.0
+    C = 0.1 * torch.randn((B, NH, dqk, dhv), device="cuda", generator=g)
+    n = [0.1 * torch.randn((B, NH, dqk), device="cuda", generator=g), torch.empty((B, NH, dqk), device="cuda")]
+    m = [torch.zeros((B, NH), device="cuda"), torch.empty((B, NH), device="cuda")]
+    h = torch.empty((B, NH, dhv), device="cuda", dtype=bf)
+    outs = [{"h": h, "C": C, "n": n[1], "m": m[1]}, {"h": h, "C": C, "n": n[0], "m": m[0]}]
+    it = [0]
+
+    def step():
+        i = it[0] & 1
+        tfla.mlstm_step(q, k, v, ip, fp, C, n[i], m[i], variant=variant, eps=1e-6, out=outs[i])
+        it[0] += 1
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    tfla.profile_enable(2 * (args.steps + 1))
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = tfla.profile_read()
+    tfla.profile_enable(0)
+    kms = prof["recurrent_step"]["ms"] / max(1, prof["recurrent_step"]["launches"])
+    # per step and head (App. F.2, memory operations of the recurrent formulation, fp32 states and gates)
+    per_head = 2 * 4 + 2 * (dhv + dqk) * 2 + 2 * (dhv * dqk + (dqk + 1 if variant == wl.EXP else 0)) * 4
+    byts = per_head * B * NH
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import mlstm_oracle as orc
+        T = 256
+        f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+        rep = lambda t: np.repeat(f64(t).reshape((B * NH, 1) + tuple(t.shape[2:])), T, axis=1)
+        c0 = time.perf_counter()
+        orc.recurrent_fwd(rep(q), rep(k), rep(v), np.repeat(f64(ip).reshape(B * NH, 1), T, axis=1),
+                          np.repeat(f64(fp).reshape(B * NH, 1), T, axis=1), f64(C).reshape(B * NH, dqk, dhv),
+                          f64(n[0]).reshape(B * NH, dqk), f64(m[0]).reshape(B * NH), variant=variant, eps=1e-6)
+        c1 = time.perf_counter()
+        cpu = {"value": B * T / (c1 - c0), "unit": "tokens/s", "cores": int(orc.num_threads()), "kind": "oracle",
+               "seconds": c1 - c0, "sample": "%d steps of the fp64 step-by-step recurrence for all %d heads" % (T, B * NH)}
+    line = {"metric": "mLSTM recurrent step (generation) tokens/s at NH=8, dqk=256, dhv=512", "value": B / (ms * 1e-3),
+            "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "step", "variant": "mLSTMexp" if variant == wl.EXP else "mLSTMsig", "B": B, "NH": NH,
+                       "dqk": dqk, "dhv": dhv, "state": "fp32, updated in place"},
+            "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": byts / (kms * 1e-3) / 1e9,
+                         "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": byts / (kms * 1e-3) / PEAK_HBM, "traffic": None,
+                         "avg_launch_ms": kms, "algorithmic_bytes_per_launch": byts},
+            "cpu_baseline": cpu}
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -116,6 +187,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     tfla.load_library()   # fails loudly if the HIP library is missing
+    if args.workload == "step":
+        return step_bench(args)
 
     w = wl.CONFIGS[args.workload]
     if args.chunk:

@@ -117,6 +117,30 @@ TFLA_API int tfla_mlstm_bwd(const void* q, const void* k, const void* v,
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * One recurrent step (Sec. 2.1 for TFLA_EXP, Sec. 4.1 for TFLA_SIG): the form used for
+ * generation.  For every (batch, head): m' = max(log sigma(f~) + m, i~), C' = f' C + i' k v^T,
+ * n' = f' n + i' k with the stabilised gates f' = exp(log sigma(f~) + m - m'), i' = exp(i~ - m'),
+ * and h = C'^T q~ / (max{|n'^T q~|, exp(-m')} + eps), q~ = q / sqrt(dqk).  TFLA_SIG: C' =
+ * sigma(f~) C + sigma(i~) k v^T, h = C'^T q~.  The state is the one tfla_mlstm_fwd returns
+ * (Cn, nn, mn) and accepts (C0, n0, m0), so a prompt processed by tfla_mlstm_fwd can be
+ * continued step by step.
+ *   in : q, k (B, NH, dqk), v (B, NH, dhv) in `dtype`; i_pre, f_pre (B, NH) float;
+ *        C (B, NH, dqk, dhv), n (B, NH, dqk), m (B, NH) float: the state before the step
+ *        (n and m both NULL = zero; ignored for TFLA_SIG).
+ *   out: h (B, NH, dhv) in `dtype`; C_out, n_out, m_out: the state after the step.  C_out may be
+ *        the same buffer as C (updated in place); n_out and m_out must be buffers different from
+ *        n and m (they are read by every workgroup of a head) and are required for TFLA_EXP;
+ *        for TFLA_SIG they are zero-filled when non-NULL.
+ *   dqk, dhv: multiples of 64 in [64, 512]; B * NH <= 65535.  No workspace is needed.
+ */
+TFLA_API int tfla_mlstm_step(const void* q, const void* k, const void* v,
+                    const float* i_pre, const float* f_pre,
+                    const float* C, const float* n, const float* m,
+                    int B, int NH, int dqk, int dhv,
+                    int variant, int dtype, float eps,
+                    void* h, float* C_out, float* n_out, float* m_out, void* stream);
+
+/*
  * Bytes of workspace the call with these arguments needs (host function, launches nothing).
  * Returns 0 if the arguments are invalid.
  */

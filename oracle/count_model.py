@@ -72,3 +72,19 @@ def l_opt_runtime(dhv, p_qk, I_acc, F_causal=0.5, bytes_Cmn=4):
     """Runtime-optimal chunk size (App. G.4)."""
     return math.sqrt((2 * dhv * dhv * p_qk + 5 + 2 * I_acc * dhv * dhv * p_qk * bytes_Cmn)
                      / (2 * F_causal * (dhv * (1 + p_qk) + 3) + 1))
+
+
+def bytes_recurrent_step_exp(dqk, dhv, bytes_qkv=2, bytes_if=4, bytes_Cmn=4):
+    """Memory operations of one step of the recurrent mLSTMexp for one head, states materialised
+    after every step (App. F.2, memory operation counts of the recurrent formulation): loads
+    q, k, v, the two gates and (C, n, m); stores h and (C, n, m)."""
+    load = (2 * dqk + dhv) * bytes_qkv + 2 * bytes_if + (dqk * dhv + dqk + 1) * bytes_Cmn
+    store = dhv * bytes_qkv + (dqk * dhv + dqk + 1) * bytes_Cmn
+    return load + store
+
+
+def bytes_recurrent_step_sig(dqk, dhv, bytes_qkv=2, bytes_if=4, bytes_Cmn=4):
+    """The same for mLSTMsig: no normaliser and no max state."""
+    load = (2 * dqk + dhv) * bytes_qkv + 2 * bytes_if + dqk * dhv * bytes_Cmn
+    store = dhv * bytes_qkv + dqk * dhv * bytes_Cmn
+    return load + store

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "lib", "libtfla_mlstm.so")
 _lib = None
 
-EXPORTS = ("tfla_mlstm_fwd", "tfla_mlstm_bwd", "tfla_mlstm_workspace_bytes", "tfla_mlstm_check",
+EXPORTS = ("tfla_mlstm_fwd", "tfla_mlstm_bwd", "tfla_mlstm_step", "tfla_mlstm_workspace_bytes", "tfla_mlstm_check",
            "tfla_status_string", "tfla_version", "tfla_profile_enable", "tfla_profile_read",
            "tfla_profile_kernels")
 
@@ -44,6 +44,8 @@ def load_library():
     lib.tfla_mlstm_bwd.restype = ci
     lib.tfla_mlstm_bwd.argtypes = [vp, vp, vp, fp, fp, fp, fp, fp, fp, fp, vp, fp, ci, ci, ci, ci, ci, ci, ci, ci, cf,
                                    vp, vp, vp, fp, fp, fp, vp, sz, vp, sz, vp]
+    lib.tfla_mlstm_step.restype = ci
+    lib.tfla_mlstm_step.argtypes = [vp, vp, vp, fp, fp, fp, fp, fp, ci, ci, ci, ci, ci, ci, cf, vp, fp, fp, fp, vp]
     lib.tfla_mlstm_workspace_bytes.restype = sz
     lib.tfla_mlstm_workspace_bytes.argtypes = [ci] * 9
     lib.tfla_mlstm_check.restype = ci
@@ -191,4 +193,34 @@ def mlstm_bwd(q, k, v, i_pre, f_pre, dH, n_out=None, m_out=None, C0=None, n0=Non
     if rc != 0:
         raise TflaError(rc, "tfla_mlstm_bwd")
     o["workspace"] = workspace
+    return o
+
+
+def mlstm_step(q, k, v, i_pre, f_pre, C, n=None, m=None, variant=EXP, eps=1e-6, stream=None,
+               out: Optional[Dict] = None, inplace_C: bool = False) -> Dict:
+    """tfla_mlstm_step on torch device tensors.  q, k: (B,NH,dqk); v: (B,NH,dhv); i_pre, f_pre: (B,NH);
+    C: (B,NH,dqk,dhv) fp32, n: (B,NH,dqk), m: (B,NH).  Returns h and the new state C, n, m."""
+    import torch
+    lib = load_library()
+    B, NH, dqk = q.shape
+    dhv = v.shape[-1]
+    dtype = BF16 if q.dtype == torch.bfloat16 else F32
+    td, f32 = _torch_dtype(dtype), torch.float32
+    _want(q, td, (B, NH, dqk), "q"); _want(k, td, (B, NH, dqk), "k"); _want(v, td, (B, NH, dhv), "v")
+    _want(i_pre, f32, (B, NH), "i_pre"); _want(f_pre, f32, (B, NH), "f_pre")
+    _want(C, f32, (B, NH, dqk, dhv), "C"); _want(n, f32, (B, NH, dqk), "n"); _want(m, f32, (B, NH), "m")
+    dev = q.device
+    o = out if out is not None else {}
+    if "h" not in o:
+        o["h"] = torch.empty((B, NH, dhv), dtype=td, device=dev)
+    if "C" not in o:
+        o["C"] = C if inplace_C else torch.empty_like(C)
+    if "n" not in o:
+        o["n"] = torch.empty((B, NH, dqk), dtype=f32, device=dev)
+        o["m"] = torch.empty((B, NH), dtype=f32, device=dev)
+    rc = lib.tfla_mlstm_step(_ptr(q), _ptr(k), _ptr(v), _ptr(i_pre), _ptr(f_pre), _ptr(C), _ptr(n), _ptr(m),
+                             B, NH, dqk, dhv, int(variant), dtype, float(eps),
+                             _ptr(o["h"]), _ptr(o["C"]), _ptr(o["n"]), _ptr(o["m"]), _stream_handle(stream))
+    if rc != 0:
+        raise TflaError(rc, "tfla_mlstm_step")
     return o

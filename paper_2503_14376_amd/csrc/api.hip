@@ -118,9 +118,10 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
 
 // ---- optional per-kernel timing with HIP events on the caller's stream -------------------
 enum { K_GATES = 0, K_BWD_PREP, K_REC_FWD, K_REC_BWD, K_TILE_H, K_TILE_DV, K_TILE_DQ, K_TILE_DK, K_GATE_GRADS,
-       K_STATE_DOT, K_FILL, K_COUNT };
+       K_STATE_DOT, K_FILL, K_STEP, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"gates", "gate_bwd_prep", "recurrent_fwd", "recurrent_bwd", "tile_H",
-                                           "tile_dV", "tile_dQ", "tile_dK", "gate_grads", "state_dot", "fill_zero"};
+                                           "tile_dV", "tile_dQ", "tile_dK", "gate_grads", "state_dot", "fill_zero",
+                                           "recurrent_step"};
 struct Profiler {
     bool on = false;
     int cap = 0, used = 0;
@@ -224,7 +225,7 @@ const char* tfla_status_string(int status) {
         case TFLA_ERR_CHUNK: return "chunk must be a multiple of 64 in [64, 2048] that divides T (T/chunk <= 4096)";
         case TFLA_ERR_ENUM: return "unknown variant, dtype or direction";
         case TFLA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
-        case TFLA_ERR_STATE: return "initial state must be given completely (C0, n0, m0) or not at all";
+        case TFLA_ERR_STATE: return "state must be given completely (C, n, m) or not at all; n_out/m_out must not alias n/m";
         default: break;
     }
     if (status > 0) return hipGetErrorString((hipError_t)status);
@@ -386,6 +387,33 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
     gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
     gg.BHT = d.BHT; gg.bsum = w.bsum;
     TFLA_LAUNCH(K_GATE_GRADS, launch_gate_grads(gg, (int)d.BH, s));
+    return TFLA_OK;
+}
+
+int tfla_mlstm_step(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                    const float* C, const float* n, const float* m, int B, int NH, int dqk, int dhv, int variant,
+                    int dtype, float eps, void* h, float* C_out, float* n_out, float* m_out, void* stream) {
+    if (variant != TFLA_EXP && variant != TFLA_SIG) return TFLA_ERR_ENUM;
+    if (dtype != TFLA_F32 && dtype != TFLA_BF16) return TFLA_ERR_ENUM;
+    if (B <= 0 || NH <= 0 || (long)B * NH > 65535) return TFLA_ERR_SHAPE;
+    if (dqk < 64 || dqk > 512 || dqk % 64 != 0 || dhv < 64 || dhv > 512 || dhv % 64 != 0) return TFLA_ERR_SHAPE;
+    if (!q || !k || !v || !i_pre || !f_pre || !C || !C_out || !h) return TFLA_ERR_NULL;
+    if (variant == TFLA_EXP) {
+        if ((n != nullptr) != (m != nullptr)) return TFLA_ERR_STATE;
+        if (!n_out || !m_out) return TFLA_ERR_NULL;
+        if (n_out == n || m_out == m) return TFLA_ERR_STATE;    // every column slab reads n and m
+    }
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    StepArgs a;
+    a.q = q; a.k = k; a.v = v; a.i_pre = i_pre; a.f_pre = f_pre;
+    a.C = C; a.n = variant == TFLA_EXP ? n : nullptr; a.m = variant == TFLA_EXP ? m : nullptr;
+    a.C_out = C_out; a.n_out = variant == TFLA_EXP ? n_out : nullptr; a.m_out = variant == TFLA_EXP ? m_out : nullptr;
+    a.h = h; a.dqk = dqk; a.dhv = dhv; a.variant = variant; a.dtype = dtype; a.eps = eps;
+    TFLA_LAUNCH(K_STEP, launch_step(a, B * NH, s));
+    if (variant == TFLA_SIG) {
+        if (n_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(n_out, (long)B * NH * dqk, s));
+        if (m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(m_out, (long)B * NH, s));
+    }
     return TFLA_OK;
 }
 

@@ -47,6 +47,18 @@ hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
 hipError_t launch_fill_zero(float* p, long n, hipStream_t s);
 hipError_t launch_state_dot(const float* A, const float* Bm, float* out, long per, int BH, hipStream_t s);
 
+// ---- single recurrent step (Sec. 2.1, Sec. 4.1) ------------------------------------------------
+struct StepArgs {
+    const void* q; const void* k; const void* v;   // (BH, dqk), (BH, dqk), (BH, dhv)
+    const float* i_pre; const float* f_pre;        // (BH)
+    const float* C; const float* n; const float* m;   // state before the step; n, m may be NULL (zero)
+    float* C_out; float* n_out; float* m_out;      // state after the step; n_out, m_out may be NULL
+    void* h;                                       // (BH, dhv)
+    int dqk, dhv, variant, dtype;
+    float eps;
+};
+hipError_t launch_step(const StepArgs& a, int BH, hipStream_t s);
+
 // ---- inter-chunk recurrence (App. B.2 "Inter-chunk Recurrent Contribution"; App. B.3) -------
 // state <- gbar[k] * state + (rs (.) X_k)^T Y_k, chunk by chunk; the state *before* each
 // update is written to slot k.

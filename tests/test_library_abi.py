@@ -144,3 +144,24 @@ def test_backward_argument_validation_happens_before_any_launch(tfla):
     assert call(ws=0) == -5
     assert call(ws_bytes=4096) == -5
     assert call(fws=2, fws_bytes=1024) == -5       # a forward workspace that is too small to be one
+
+
+def test_step_argument_validation_happens_before_any_launch(tfla):
+    lib = tfla.load_library()
+    P = lambda x: ctypes.c_void_p(x * 4096) if x else None
+
+    def call(q=1, C=1, n=2, m=3, h=1, C_out=1, n_out=4, m_out=5, dqk=256, dhv=512, variant=0, dtype=1, B=2, NH=8):
+        return lib.tfla_mlstm_step(P(q), P(1), P(1), P(1), P(1), P(C), P(n), P(m), B, NH, dqk, dhv, variant, dtype, 1e-6,
+                                   P(h), P(C_out), P(n_out), P(m_out), None)
+    assert call(q=0) == -1
+    assert call(C=0) == -1
+    assert call(h=0) == -1
+    assert call(n_out=0) == -1                     # the exponential-gate step returns n and m
+    assert call(dqk=96) == -2
+    assert call(dhv=1024) == -2
+    assert call(B=0) == -2
+    assert call(variant=3) == -4
+    assert call(dtype=2) == -4
+    assert call(n=2, m=0) == -6                    # state only partly given
+    assert call(n=4, n_out=4) == -6                # n_out must not alias n
+    assert call(m=5, m_out=5) == -6

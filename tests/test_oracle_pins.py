@@ -335,3 +335,20 @@ def test_p7_count_model_self_consistency():
     assert abs(Ls[np.argmin(tau)] * 10 - cm.l_opt_runtime(dhv, p, a_f / a_b)) < 0.5
     # L=1 and L=T limits move between the recurrent and the parallel counts (App. G.5, item 2)
     assert cm.flops_chunkwise_sig(T, 1, dqk, dhv) / cm.flops_recurrent_sig(T, dqk, dhv) < 1.01
+
+
+def test_p7_recurrent_step_memory_operations():
+    """App. F.2: totals of the recurrent formulation's memory-operation table.  Loads and stores of one
+    step add up to 2 bytes_if + 2 (d_hv + d_qk) bytes_qkv + 2 (d_hv d_qk + d_qk + 1) bytes_Cmn for
+    mLSTMexp and to the same without the n and m terms for mLSTMsig (the printed table swaps the two
+    totals between its columns: the load and store rows, which it is the sum of, decide)."""
+    from oracle import count_model as cm
+    for dqk, dhv in ((64, 64), (256, 512)):
+        for bq, bi, bc in ((2, 2, 4), (2, 4, 4), (4, 4, 4)):
+            exp_total = 2 * bi + 2 * (dhv + dqk) * bq + 2 * (dhv * dqk + dqk + 1) * bc
+            sig_total = 2 * bi + 2 * (dhv + dqk) * bq + 2 * dhv * dqk * bc
+            assert cm.bytes_recurrent_step_exp(dqk, dhv, bq, bi, bc) == exp_total
+            assert cm.bytes_recurrent_step_sig(dqk, dhv, bq, bi, bc) == sig_total
+    # at the 7B head shape the matrix memory is > 99 % of the traffic: the step is bound by 2 d_qk d_hv floats
+    tot = cm.bytes_recurrent_step_exp(256, 512)
+    assert 2 * 256 * 512 * 4 / tot > 0.99
