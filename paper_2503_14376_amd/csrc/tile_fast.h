@@ -226,11 +226,20 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     float nrm = 0.0f;
     if (MODE == MODE_H) {
         if (a.variant == 0) {
-            float dot = 0.0f;
+            // q~ . n_{k-1} from the X fragments in registers: eight consecutive n per fragment (two 16-byte
+            // LDS reads), four partial sums to shorten the dependency chain
+            float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int ks = 0; ks < KS1; ++ks)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) dot += E::frag_elem(xf[ks], e) * ldsN[16 * ks + 8 * g + e];
+            for (int ks = 0; ks < KS1; ++ks) {
+                const f32x4 n0 = *reinterpret_cast<const f32x4*>(&ldsN[16 * ks + 8 * g]);
+                const f32x4 n1 = *reinterpret_cast<const f32x4*>(&ldsN[16 * ks + 8 * g + 4]);
+                const u32x4 w = __builtin_bit_cast(u32x4, xf[ks].v);
+                d4[0] += bf16_lo_to_f32(w[0]) * n0[0] + bf16_hi_to_f32(w[0]) * n0[1];
+                d4[1] += bf16_lo_to_f32(w[1]) * n0[2] + bf16_hi_to_f32(w[1]) * n0[3];
+                d4[2] += bf16_lo_to_f32(w[2]) * n1[0] + bf16_hi_to_f32(w[2]) * n1[1];
+                d4[3] += bf16_lo_to_f32(w[3]) * n1[2] + bf16_hi_to_f32(w[3]) * n1[3];
+            }
+            float dot = (d4[0] + d4[1]) + (d4[2] + d4[3]);
             dot += __shfl_xor(dot, 32, 64);
             nrm = dot * srl;
         }
