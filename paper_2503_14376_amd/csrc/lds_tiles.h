@@ -67,24 +67,6 @@ __device__ __forceinline__ void dma4(const void* gbase_uniform, uint32_t voff, u
                  :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
 }
 
-// 2-byte stores of the low / high half of w to (uniform base + per-lane byte offset): the address
-// needs no vector arithmetic
-__device__ __forceinline__ void store_bf16_lo(void* base_uniform, uint32_t voff, uint32_t w) {
-    const uint64_t gb = (uint64_t)(uintptr_t)base_uniform;
-    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
-    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
-    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
-    // s_nop 4: 5 wait states between the SGPR write of the base and this read (see dma16)
-    asm volatile("s_nop 4\n\tglobal_store_short %0, %1, %2" :: "v"(voff), "v"(w), "s"(gu) : "memory");
-}
-__device__ __forceinline__ void store_bf16_hi(void* base_uniform, uint32_t voff, uint32_t w) {
-    const uint64_t gb = (uint64_t)(uintptr_t)base_uniform;
-    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
-    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
-    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
-    asm volatile("s_nop 4\n\tglobal_store_short_d16_hi %0, %1, %2" :: "v"(voff), "v"(w), "s"(gu) : "memory");
-}
-
 // workgroup barrier without the fence a __syncthreads() carries (that fence would wait for
 // every outstanding global->LDS load, i.e. drain the pipeline)
 __device__ __forceinline__ void barrier_nofence() { asm volatile("s_barrier" ::: "memory"); }
