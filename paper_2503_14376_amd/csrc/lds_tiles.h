@@ -56,6 +56,19 @@ __device__ __forceinline__ void dma16(const void* gbase_uniform, uint32_t voff, 
                  :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
 }
 
+// The same load without the "memory" clobber: the compiler may move ordinary LDS reads and MFMAs
+// across it (it stays ordered with the kernels' barriers and waits, which are volatile asm too).
+// For loads that are issued between matrix instructions into a stage nobody reads in that phase.
+__device__ __forceinline__ void dma16_free(const void* gbase_uniform, uint32_t voff, uint32_t lds_uniform) {
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_uniform);
+    const uint64_t gb = (uint64_t)(uintptr_t)gbase_uniform;
+    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
+    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
+    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(la), "v"(voff), "s"(gu) : "m0");
+}
+
 // Same for 64 x 4 bytes: lane l copies one dword to LDS address lds_uniform + 4 * l.
 __device__ __forceinline__ void dma4(const void* gbase_uniform, uint32_t voff, uint32_t lds_uniform) {
     const uint32_t la = __builtin_amdgcn_readfirstlane(lds_uniform);
@@ -110,6 +123,13 @@ template <int ROWS, int COLS, int NT, int KIND> struct DmaTile {
         const int wave = tid >> 6;
 #pragma unroll
         for (int j = 0; j < N; ++j) dma16(gtile, goff[j], lds + (wave + j * NWV) * 1024);
+    }
+    // the loads j = part, part + nparts, ... only (part, nparts compile-time in the callers)
+    __device__ __forceinline__ void issue_part(const bf16_t* gtile, uint32_t lds, int tid, int part, int nparts) const {
+        const int wave = tid >> 6;
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (j % nparts == part) dma16_free(gtile, goff[j], lds + (wave + j * NWV) * 1024);
     }
 };
 

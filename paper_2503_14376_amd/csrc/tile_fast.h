@@ -126,6 +126,27 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             }
         }
     };
+    // the same, spread over `nparts` calls that are placed between matrix instructions
+    auto issue_part = [&](int item, int part, int nparts) {
+        const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
+        if (item < NXS) {
+            dxs.issue_part(Xb + item * BXS, st, tid, part, nparts);
+        } else if (item < NPRE) {
+            const int sl = item - NXS;
+            ds.issue_part(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid, part, nparts);
+        } else {
+            const int ct = ct_lo + item - NPRE;
+            if (ELITE) {
+                dy.issue_part(Eb + (long)ct * BC * a.L, st, tid, part, nparts);
+                dz.issue_part(Z + (long)ct * BC * d2, st + YB, tid, part, nparts);
+            } else {
+                dy.issue_part(Y + (long)ct * BC * D1, st, tid, part, nparts);
+                dz.issue_part(Z + (long)ct * BC * d2, st + YB, tid, part, nparts);
+                if (part == 0)
+                    dma4(wcol + ct * BC, (uint32_t)(lane & 31) * 4u, w_a + (uint32_t)(((item % NS) * NW + wave) * 256));
+            }
+        }
+    };
     // loads of this wave issued after those of item i and still allowed in flight while waiting for i
     auto pending_after = [&](int i) {
         int p = 0;
@@ -188,20 +209,38 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         wait_vmcnt_dyn(pending_after(NXS + i));
         if (i == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         barrier_nofence();
-        if (NXS + i + NS - 1 < NI) issue(NXS + i + NS - 1);
+        const bool req = NXS + i + NS - 1 < NI;
         const char* sb = smem + ((NXS + i) % NS) * STAGE;
-        {
-            constexpr int NF = (BCS / 16) * NB;
-            frag b[BCS / 16][NB];
+        constexpr int KSS = BCS / 16, NF = KSS * NB;
+        if constexpr (OCC == 1) {
+            frag b[KSS][NB];
+            // one wavefront per SIMD: nothing else hides the time the request spends in the memory
+            // pipeline's queue, so it is spread between the matrix instructions; all fragments of the
+            // slice are read first
 #pragma unroll
-            for (int ks = 0; ks < BCS / 16; ++ks)
+            for (int ks = 0; ks < KSS; ++ks)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
                     b[ks][nb].v = STT ? rzn.load(sb, nb, 16 * ks, 16 * ks + 4) : rs_.load(sb, ks, nb);
 #pragma unroll
-            for (int ks = 0; ks < BCS / 16; ++ks)
+            for (int ks = 0; ks < KSS; ++ks) {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks][nb], xf[i * (BCS / 16) + ks], acc[nb]);
+                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks][nb], xf[i * KSS + ks], acc[nb]);
+                if (req) issue_part(NXS + i + NS - 1, ks, KSS);
+            }
+        } else {
+            if (req) issue(NXS + i + NS - 1);
+            frag b[KSS][NB];
+#pragma unroll
+            for (int ks = 0; ks < KSS; ++ks)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    b[ks][nb].v = STT ? rzn.load(sb, nb, 16 * ks, 16 * ks + 4) : rs_.load(sb, ks, nb);
+#pragma unroll
+            for (int ks = 0; ks < KSS; ++ks)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks][nb], xf[i * KSS + ks], acc[nb]);
+            // LDS reads run PF fragments ahead of the MFMAs that consume them
             constexpr int PF = NF < 4 ? NF : 4;
             constexpr int DSR = STT ? 2 : 1;            // LDS reads per fragment
 #pragma unroll
@@ -257,9 +296,13 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         const int i = NPRE + ct - ct_lo;
         wait_vmcnt_dyn(pending_after(i));
         barrier_nofence();
-        if (i + NS - 1 < NI) issue(i + NS - 1);
+        const bool req = i + NS - 1 < NI;
         const int cs = ct * BC;
-        if (UPPER ? (cs + 31 < wr0) : (cs > wr0 + 31)) continue;      // fully masked for this wave
+        const bool masked = UPPER ? (cs + 31 < wr0) : (cs > wr0 + 31);   // fully masked for this wave
+        // with one wavefront per SIMD the request is spread between the matrix instructions below
+        constexpr bool SPREAD = false;   // measured slower: the groups lose the read-ahead across their boundaries
+        if (req && (!SPREAD || masked)) issue(i + NS - 1);
+        if (masked) continue;
         const bool diag = UPPER ? (cs < wr0 + 31) : (cs + 31 > wr0);
         const char* yb = smem + (i % NS) * STAGE;
         const char* zb = yb + YB;
@@ -273,7 +316,28 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         f32x16 s;
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.0f;
-        {
+        if constexpr (SPREAD) {
+            constexpr int G = 4, KG = KS1 / G;
+#pragma unroll
+            for (int gq = 0; gq < G; ++gq) {
+                frag ya[KG];
+#pragma unroll
+                for (int ks = 0; ks < KG; ++ks) ya[ks].v = ry.load(yb, gq * KG + ks, 0);
+#pragma unroll
+                for (int ks = 0; ks < KG; ++ks) s = E::mma(ya[ks], xf[gq * KG + ks], s);
+                constexpr int PF = KG < 4 ? KG : 4;
+#pragma unroll
+                for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+                for (int q = 0; q < KG - PF; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+#pragma unroll
+                for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (req) issue_part(i + NS - 1, gq, G);
+            }
+        } else {
             frag ya[KS1];
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks) ya[ks].v = ry.load(yb, ks, 0);
