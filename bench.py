@@ -76,9 +76,9 @@ def algorithmic_bytes(w: wl.Workload, es: int):
 MEASURED_TRAFFIC_C4 = {
     "recurrent_kernel": 226.0e6 + 148.1e6,
     "tile_kernel<H>": 405.4e6 + 134.7e6,
-    "tile_kernel<dV>": 406.5e6 + 134.2e6,
+    "tile_kernel<dV>": 406.7e6 + 134.2e6,
     "tile_kernel<dQ>": 538.7e6 + 105.9e6,
-    "tile_kernel<dK>": 455.2e6 + 67.6e6,
+    "tile_kernel<dK>": 454.8e6 + 67.6e6,
 }
 
 

@@ -50,7 +50,8 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
     using frag = E::frag;
     constexpr int NTP = WN * 64, BM = 64, BN = WN * 32, MI = 2, KS = BK / 16;
     constexpr int XB = BK * BM * 2, YB = BK * BN * 2, STAGE = XB + YB;
-    constexpr int NS = BK == 64 ? 5 : 3;            // ring stages (the ring is 120 KB or 144 KB of LDS)
+    constexpr int NS = BK == 64 ? 6 : 3;            // ring stages (the ring is 144 KB of LDS)
+    constexpr int NH = NS - 3;                      // earlier iterations whose stores are younger than the awaited piece
     using DX = DmaTile<BK, BM, NTP, SWZ_T>;         // the producers' share of a piece
     using DY = DmaTile<BK, BN, NTP, SWZ_T>;
     constexpr int NX = DX::N;                       // 16-byte chunks of the X piece per producer lane
@@ -58,7 +59,7 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
     constexpr int CPC = DY::N;                      // loads per consumer and piece (Y)
     constexpr int NST = 4;                          // state stores per consumer at a chunk boundary
     constexpr int STEADY = (NS - 2) * CPP, STEADY_C = (NS - 2) * CPC;
-    static_assert(STEADY + 3 <= 63 && STEADY_C + 3 * NST <= 63, "wait counts must fit the 6-bit counter");
+    static_assert(STEADY + NH + 1 <= 63 && STEADY_C + (NH + 1) * NST <= 63, "wait counts must fit the 6-bit counter");
     static_assert(CPC % KS == 0, "Y requests are spread evenly over the k steps");
 
     __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
@@ -175,8 +176,8 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
 
         // Iteration i (consumers multiply piece i): request piece i + NS - 1 into the slot of piece
         // i - 1, which the consumers have left; rescale piece i + 1.  (sub, step, slot) describe
-        // piece i; st1, st2 count this wave's stores of the two previous iterations.
-        int sub = 0, step = 0, slot = 0, st1 = 0, st2 = 0;
+        // piece i; sth[] counts this wave's stores of the NH previous iterations.
+        int sub = 0, step = 0, slot = 0, sth[NH + 1] = {};
         for (int i = 0; i < P; ++i) {
             // the rescaled chunks (plain LDS writes) must have landed before the barrier hands them over
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -204,11 +205,16 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
                 // issued since (this iteration's and those of the NS - 3 iterations before)
                 int ahead = P - 2 - i;
                 ahead = ahead > NS - 2 ? NS - 2 : ahead;
-                rescale(slot1, step1, sub1 == PPC - 1, ahead * CPP + st0 + (NS >= 4 ? st1 : 0) + (NS >= 5 ? st2 : 0));
+                int pending = ahead * CPP + st0;
+#pragma unroll
+                for (int h = 0; h < NH; ++h) pending += sth[h];
+                rescale(slot1, step1, sub1 == PPC - 1, pending);
             }
             TFLA_RTL(4 * i + 2);
             sub = sub1; step = step1; slot = slot1;
-            st2 = st1; st1 = st0;
+#pragma unroll
+            for (int h = NH; h > 0; --h) sth[h] = sth[h - 1];
+            sth[0] = st0;
         }
         if (n_owner && a.nfinal) a.nfinal[(long)bh * a.d1 + m0 + lane] = nacc;
     } else {
@@ -255,7 +261,7 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
                 ++requested;
             }
         wait_vmcnt_dyn((requested - 1) * CPC);      // this wave's part of piece 0 has landed
-        int sub = 0, step = 0, slot = 0, st1 = 0, st2 = 0;
+        int sub = 0, step = 0, slot = 0, sth[NH + 1] = {};
         for (int i = 0; i < P; ++i) {
             barrier_nofence();
             TFLA_RTL(4 * i);
@@ -318,17 +324,21 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
             if (req) request_end();
             TFLA_RTL(4 * i + 2);
             // this wave's part of Y of piece i + 1 must have landed before the next barrier; younger
-            // than it are the requests made after it and the stores of this and the two previous
+            // than it are the requests made after it and the stores of this and the NH previous
             // iterations
             if (i + 1 < P) {
                 int ahead = P - 2 - i;
                 ahead = ahead > NS - 2 ? NS - 2 : ahead;
-                const int pending = ahead * CPC + st0 + (NS >= 4 ? st1 : 0) + (NS >= 5 ? st2 : 0);
+                int pending = ahead * CPC + st0;
+#pragma unroll
+                for (int h = 0; h < NH; ++h) pending += sth[h];
                 if (pending == STEADY_C) wait_vmcnt<STEADY_C>();
                 else if (pending == STEADY_C + NST) wait_vmcnt<STEADY_C + NST>();
                 else wait_vmcnt_dyn(pending);
             }
-            st2 = st1; st1 = st0;
+#pragma unroll
+            for (int h = NH; h > 0; --h) sth[h] = sth[h - 1];
+            sth[0] = st0;
             if (++sub == PPC) { sub = 0; ++step; }
             if (++slot == NS) slot = 0;
         }
