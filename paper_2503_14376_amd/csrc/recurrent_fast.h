@@ -36,8 +36,11 @@ namespace tfla {
 // kept in LDS during the run (a global store would disturb the load counters being studied)
 static __device__ unsigned long long tfla_rec_timeline[8192];
 #define TFLA_RTL_DECL __shared__ unsigned long long tl_lds[2][128];
-#define TFLA_RTL(slot) if ((tid & 255) == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && (slot) >= 0 && (slot) < 128) tl_lds[tid >> 8][(slot)] = __builtin_amdgcn_s_memtime()
-#define TFLA_RTL_FLUSH __syncthreads(); if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) for (int q_ = tid; q_ < 256; q_ += blockDim.x) tfla_rec_timeline[(q_ >> 7) * 4096 + (q_ & 127)] = tl_lds[q_ >> 7][q_ & 127];
+#ifndef TFLA_TL_BY
+#define TFLA_TL_BY 0
+#endif
+#define TFLA_RTL(slot) if ((tid & 255) == 0 && blockIdx.x == 0 && blockIdx.y == TFLA_TL_BY && blockIdx.z == 0 && (slot) >= 0 && (slot) < 128) tl_lds[tid >> 8][(slot)] = __builtin_amdgcn_s_memtime()
+#define TFLA_RTL_FLUSH __syncthreads(); if (blockIdx.x == 0 && blockIdx.y == TFLA_TL_BY && blockIdx.z == 0) for (int q_ = tid; q_ < 256; q_ += blockDim.x) tfla_rec_timeline[(q_ >> 7) * 4096 + (q_ & 127)] = tl_lds[q_ >> 7][q_ & 127];
 #else
 #define TFLA_RTL_DECL
 #define TFLA_RTL(slot)
@@ -129,9 +132,10 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
         // Rescale, in place, this wave's own chunks of the X piece in `slot` (piece of chunk step
         // `stp`, last piece of its chunk if `closes`), after waiting until at most `pending` younger
         // operations of this wave are outstanding.
-        auto rescale = [&](int slot, int stp, bool closes, int pending) {
+        auto rescale = [&](int slot, int stp, bool closes, int pending, int tl = -1) {
             if (pending == STEADY) wait_vmcnt<STEADY>();
             else wait_vmcnt_dyn(pending);
+            TFLA_RTL(tl);
             char* xt = smem + slot * STAGE;
 #pragma unroll
             for (int j = 0; j < NX; ++j) {
@@ -208,7 +212,7 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
                 int pending = ahead * CPP + st0;
 #pragma unroll
                 for (int h = 0; h < NH; ++h) pending += sth[h];
-                rescale(slot1, step1, sub1 == PPC - 1, pending);
+                rescale(slot1, step1, sub1 == PPC - 1, pending, 4 * i + 3);
             }
             TFLA_RTL(4 * i + 2);
             sub = sub1; step = step1; slot = slot1;
@@ -280,26 +284,35 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
                 const int kc = a.reverse ? a.Nc - 1 - step : step;
                 if (a.stT) {
                     st0 = NST;
-                    // through a private LDS tile [32 n][32 m] per 32-row block (16-byte chunks XOR-swizzled
-                    // by the row) so that the state leaves in 64-byte row segments
+                    // through a private LDS tile [16 n][64 m] per half of the wave's 32 columns (16-byte chunks
+                    // XOR-swizzled by the row) so that the state leaves in whole 128-byte lines
                     char* ot = stage_out + wc * 2048;
                     char* gdst = reinterpret_cast<char*>(a.stT) +
                                  ((((long)bh * a.Nc + kc) * a.d2 + n0 + wc * 32) * a.d1 + m0) * 2;
 #pragma unroll
-                    for (int mi = 0; mi < MI; ++mi) {
+                    for (int h = 0; h < 2; ++h) {
+                        if ((l32 >> 4) == h) {
+                            const int n = l32 & 15;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            uint2 w;
-                            w.x = pack_bf16x2(acc[mi][4 * j], acc[mi][4 * j + 1]);
-                            w.y = pack_bf16x2(acc[mi][4 * j + 2], acc[mi][4 * j + 3]);
-                            *reinterpret_cast<uint2*>(ot + l32 * 64 + ((j ^ ((l32 >> 1) & 3)) * 16) + 8 * g) = w;
+                            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    uint2 w;
+                                    w.x = pack_bf16x2(acc[mi][4 * j], acc[mi][4 * j + 1]);
+                                    w.y = pack_bf16x2(acc[mi][4 * j + 2], acc[mi][4 * j + 3]);
+                                    *reinterpret_cast<uint2*>(ot + n * 128 + (((4 * mi + j) ^ (n & 7)) * 16) + 8 * g) = w;
+                                }
                         }
+                        // (compiler-level ordering of the differently typed LDS accesses; the hardware runs
+                        // one wavefront's LDS operations in order)
+                        asm volatile("" ::: "memory");
 #pragma unroll
                         for (int q = 0; q < 2; ++q) {
-                            const int n = q * 16 + (lane >> 2), c = lane & 3;
-                            const u32x4 w = *reinterpret_cast<const u32x4*>(ot + n * 64 + ((c ^ ((n >> 1) & 3)) * 16));
-                            *reinterpret_cast<u32x4*>(gdst + ((long)n * a.d1 + 32 * mi + 8 * c) * 2) = w;
+                            const int n = q * 8 + (lane >> 3), c = lane & 7;
+                            const u32x4 w = *reinterpret_cast<const u32x4*>(ot + n * 128 + ((c ^ (n & 7)) * 16));
+                            *reinterpret_cast<u32x4*>(gdst + ((long)(16 * h + n) * a.d1 + 8 * c) * 2) = w;
                         }
+                        asm volatile("" ::: "memory");
                     }
                 }
                 const float gb = ldsG[slot][lane];
