@@ -165,6 +165,9 @@ def main() -> int:
     ap.add_argument("--fwd-only", action="store_true")
     ap.add_argument("--recompute", action="store_true",
                     help="do not hand the forward workspace to the backward call (gates and chunk states are recomputed)")
+    ap.add_argument("--layer", action="store_true",
+                    help="time the layer entry points (gate soft-cap 15, cell, LayerNorm, output gate) instead of the "
+                         "cell alone; a secondary line, the default line is the cell")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -200,18 +203,31 @@ def main() -> int:
     do_bwd = not args.fwd_only
     if do_bwd and not w.backward:
         w = dataclasses.replace(w, backward=True)
-    d = wl.make_inputs(w)
-    dev = gu.dev_inputs(w, d)
+    d = wl.make_layer_inputs(w) if args.layer else wl.make_inputs(w)
+    dev = {key: gu.to_dev(val, w.dtype if key in ("q", "k", "v", "dH", "o_pre") else wl.F32) for key, val in d.items()}
     torch.cuda.synchronize()
 
     f32 = torch.float32
     B, NH, T = w.B, w.NH, w.T
-    ws_f = torch.empty(tfla.workspace_bytes(0, B, NH, T, w.dqk, w.dhv, w.chunk, w.variant, w.dtype), dtype=torch.uint8, device="cuda")
-    ws_b = torch.empty(max(1, tfla.workspace_bytes(1, B, NH, T, w.dqk, w.dhv, w.chunk, w.variant, w.dtype)) if do_bwd else 1,
+    wsb = tfla.layer_workspace_bytes if args.layer else tfla.workspace_bytes
+    ws_f = torch.empty(wsb(0, B, NH, T, w.dqk, w.dhv, w.chunk, w.variant, w.dtype), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(max(1, wsb(1, B, NH, T, w.dqk, w.dhv, w.chunk, w.variant, w.dtype)) if do_bwd else 1,
                        dtype=torch.uint8, device="cuda")
     fo, bo = {}, {}
 
+    lkw = dict(chunk=w.chunk, variant=w.variant, eps=1e-6, gate_softcap=15.0, norm_kind=tfla.NORM_LAYER, norm_eps=1e-6)
+
+    def layer_step():
+        tfla.mlstm_layer_fwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["o_pre"], dev["gamma"],
+                             dev["beta"], workspace=ws_f, out=fo, **lkw)
+        if do_bwd:
+            tfla.mlstm_layer_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], fo["H"], dev["dH"],
+                                 dev["o_pre"], dev["gamma"], dev["beta"], fo["n_out"], fo["m_out"], workspace=ws_b,
+                                 out=bo, fwd_workspace=None if args.recompute else ws_f, **lkw)
+
     def step():
+        if args.layer:
+            return layer_step()
         tfla.mlstm_fwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev.get("C0"), dev.get("n0"),
                        dev.get("m0"), chunk=w.chunk, variant=w.variant, eps=1e-6, workspace=ws_f, out=fo)
         if do_bwd:
@@ -317,7 +333,7 @@ def main() -> int:
                 "kernel_ms": {k_: round(v_, 4) for k_, v_ in kernels.items()}}
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.layer:
         from oracle import mlstm_oracle as orc
         nsl = min(16, w.B * w.NH)
         ds = wl.make_inputs(w, heads=nsl)
@@ -343,7 +359,7 @@ def main() -> int:
         "launch": "eager" if graph is None else "hip graph replay",
         "config": {"workload": w.name, "variant": "mLSTMexp" if w.variant == wl.EXP else "mLSTMsig",
                    "B": w.B, "NH": w.NH, "T": w.T, "dqk": w.dqk, "dhv": w.dhv, "chunk": w.chunk,
-                   "pass": "fwd+bwd" if do_bwd else "fwd", "states": "element type of q/k/v (bf16), fp32 accumulation"},
+                   "pass": ("layer " if args.layer else "") + ("fwd+bwd" if do_bwd else "fwd"), "states": "element type of q/k/v (bf16), fp32 accumulation"},
         "algorithmic_tflops": total_fl / 1e12,
         "mfma_frac_of_peak_whole_step": total_fl / (ms_per_step * 1e-3) / peak,
         "roofline": roof,

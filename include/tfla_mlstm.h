@@ -51,6 +51,7 @@ extern "C" {
 enum { TFLA_EXP = 0, TFLA_SIG = 1 };           /* variant: exponential / sigmoid input gate */
 enum { TFLA_F32 = 0, TFLA_BF16 = 1 };          /* dtype of q, k, v, H, dH, dq, dk, dv        */
 enum { TFLA_FWD = 0, TFLA_BWD = 1 };           /* direction for tfla_mlstm_workspace_bytes   */
+enum { TFLA_NORM_RMS = 0, TFLA_NORM_LAYER = 1 }; /* norm_kind of the layer entry points      */
 
 enum {
     TFLA_OK = 0,
@@ -139,6 +140,78 @@ TFLA_API int tfla_mlstm_step(const void* q, const void* k, const void* v,
                     int B, int NH, int dqk, int dhv,
                     int variant, int dtype, float eps,
                     void* h, float* C_out, float* n_out, float* m_out, void* stream);
+
+/*
+ * The cell inside its layer (Sec. 2.1, hidden-state output equation): soft-capped gates, the
+ * cell, the multi-head NORM and the output gate,
+ *     i~, f~ <- c tanh(i~ / c), c tanh(f~ / c)        (soft-capping equation of App. E; c = gate_softcap,
+ *                                                      0 = no cap; the paper trains with c = 15)
+ *     h~     =  cell(q, k, v, i~, f~)                  (exactly tfla_mlstm_fwd)
+ *     y      =  sigma(o~) (.) NORM(h~)                 (NORM per (batch, head, step) over dhv)
+ * NORM is the RMS norm as Sec. 4.1 writes it, x / sqrt(mean(x^2) + norm_eps) (.) gamma
+ * (TFLA_NORM_RMS), or LayerNorm, (x - mean(x)) / sqrt(var(x) + norm_eps) (.) gamma + beta
+ * (TFLA_NORM_LAYER).
+ *   in : as tfla_mlstm_fwd, plus o_pre (B, NH, T, dhv) in `dtype` or NULL (gate = 1);
+ *        gamma, beta (NH, dhv) float, each may be NULL (1 and 0; beta is ignored by the RMS norm).
+ *   out: Y (B, NH, T, dhv) in `dtype` (required); H (required): the cell output h~, which the
+ *        backward call needs; Cn, nn, mn, n_out, m_out as in tfla_mlstm_fwd.
+ *   workspace: tfla_mlstm_layer_workspace_bytes(TFLA_FWD, ...) bytes; reusable by the backward
+ *        call as fwd_workspace under the same conditions as for tfla_mlstm_fwd.
+ * Additional errors: TFLA_ERR_ENUM for an unknown norm_kind, TFLA_ERR_SHAPE for a negative
+ * gate_softcap or norm_eps.
+ */
+TFLA_API int tfla_mlstm_layer_fwd(const void* q, const void* k, const void* v,
+                         const float* i_pre, const float* f_pre,
+                         const void* o_pre, const float* gamma, const float* beta,
+                         const float* C0, const float* n0, const float* m0,
+                         int B, int NH, int T, int dqk, int dhv,
+                         int chunk, int variant, int dtype, float eps,
+                         float gate_softcap, int norm_kind, float norm_eps,
+                         void* Y, void* H, float* Cn, float* nn, float* mn,
+                         float* n_out, float* m_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of tfla_mlstm_layer_fwd: the exact derivative of the output gate and the NORM turns dY
+ * into the cell's upstream gradient, the cell's backward is tfla_mlstm_bwd's (normaliser held
+ * constant, App. B.3), and the gate gradients are taken through the soft-cap.
+ *   in : the forward inputs; H, n_out, m_out as written by the forward call; dY (B, NH, T, dhv);
+ *        dCn or NULL.
+ *   out: dq, dk, dv, d_i_pre, d_f_pre, dC0 as in tfla_mlstm_bwd; do_pre (B, NH, T, dhv) in `dtype`
+ *        (may be NULL; not written when o_pre is NULL); dgamma, dbeta (NH, dhv) float, each may be
+ *        NULL (dbeta is zero-filled for the RMS norm).  The parameter gradients are summed over
+ *        batch and time in a fixed order (bit-reproducible).
+ *   workspace: tfla_mlstm_layer_workspace_bytes(TFLA_BWD, ...) bytes, 256-byte aligned.
+ */
+TFLA_API int tfla_mlstm_layer_bwd(const void* q, const void* k, const void* v,
+                         const float* i_pre, const float* f_pre,
+                         const void* o_pre, const float* gamma, const float* beta,
+                         const float* C0, const float* n0, const float* m0,
+                         const void* H, const float* n_out, const float* m_out,
+                         const void* dY, const float* dCn,
+                         int B, int NH, int T, int dqk, int dhv,
+                         int chunk, int variant, int dtype, float eps,
+                         float gate_softcap, int norm_kind, float norm_eps,
+                         void* dq, void* dk, void* dv,
+                         float* d_i_pre, float* d_f_pre,
+                         void* do_pre, float* dgamma, float* dbeta, float* dC0,
+                         const void* fwd_workspace, size_t fwd_workspace_bytes,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace bytes of the two layer entry points (host function; 0 for invalid arguments). */
+TFLA_API size_t tfla_mlstm_layer_workspace_bytes(int direction, int B, int NH, int T, int dqk, int dhv,
+                                        int chunk, int variant, int dtype);
+
+/*
+ * Gains of the transfer-behaviour experiment (Sec. 4.1, gain equation; App. D.2): for every
+ * (batch, head) the time averages of max_i|h~_t,i| / max_i|v_t,i| (g_before) and of
+ * max_i|NORM(h~_t)_i| / max_i|v_t,i| (g_after), NORM with unit scale and no shift.
+ *   in : h, v (B, NH, T, dhv) in `dtype`; dhv a multiple of 8, at most 2048.
+ *   out: g_before, g_after (B, NH) float.
+ */
+TFLA_API int tfla_transfer_gain(const void* h, const void* v, int B, int NH, int T, int dhv,
+                       int dtype, int norm_kind, float norm_eps,
+                       float* g_before, float* g_after, void* stream);
 
 /*
  * Bytes of workspace the call with these arguments needs (host function, launches nothing).

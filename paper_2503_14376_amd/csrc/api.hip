@@ -118,10 +118,10 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
 
 // ---- optional per-kernel timing with HIP events on the caller's stream -------------------
 enum { K_GATES = 0, K_BWD_PREP, K_REC_FWD, K_REC_BWD, K_TILE_H, K_TILE_DV, K_TILE_DQ, K_TILE_DK, K_GATE_GRADS,
-       K_STATE_DOT, K_FILL, K_STEP, K_COUNT };
+       K_STATE_DOT, K_FILL, K_STEP, K_NORM_FWD, K_NORM_BWD, K_GAIN, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"gates", "gate_bwd_prep", "recurrent_fwd", "recurrent_bwd", "tile_H",
                                            "tile_dV", "tile_dQ", "tile_dK", "gate_grads", "state_dot", "fill_zero",
-                                           "recurrent_step"};
+                                           "recurrent_step", "norm_gate_fwd", "norm_gate_bwd", "transfer_gain"};
 struct Profiler {
     bool on = false;
     int cap = 0, used = 0;
@@ -166,8 +166,10 @@ void prof_collect() {
 }
 
 int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float* m0, float* wrow, float* ucol,
-              float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, float* csum, hipStream_t s) {
+              float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, float* csum, float softcap,
+              hipStream_t s) {
     GateArgs g;
+    g.softcap = softcap;
     g.i_pre = i_pre; g.f_pre = f_pre; g.m0 = d.variant == TFLA_EXP ? m0 : nullptr;
     g.T = d.T; g.L = d.L; g.Nc = d.Nc; g.variant = d.variant;
     g.qscale = 1.0f / sqrtf((float)d.dqk);
@@ -175,6 +177,154 @@ int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float
     TFLA_LAUNCH(K_GATES, launch_gates(g, (int)d.BH, s));
     return TFLA_OK;
 }
+
+int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
+             const float* n0, const float* m0, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype,
+             float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
+             void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (rc != TFLA_OK) return rc;
+    if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
+    if (variant == TFLA_EXP) {
+        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
+        if (given != 0 && given != 3) return TFLA_ERR_STATE;
+    }
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+    const FwdWs w = carve_fwd(d, workspace);
+    if (workspace_bytes < w.bytes) return TFLA_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const bool is_exp = variant == TFLA_EXP;
+
+    // 1. gates, max states
+    float* mout = (is_exp && m_out) ? m_out : w.mout;
+    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, softcap, s);
+    if (st != TFLA_OK) return st;
+
+    // 2. recurrent kernel: C_{k-1} (transposed, element type of q/k/v) and n_{k-1} for every chunk
+    RecArgs r;
+    r.X = k; r.Y = v; r.rs = w.aK; r.gbar = w.gbar; r.S0 = C0;
+    r.stT = w.stT; r.stN = nullptr; r.Sfinal = Cn; r.Sfinal2 = w.Cfin;
+    r.n0 = is_exp ? n0 : nullptr; r.nst = is_exp ? w.nst : nullptr; r.nfinal = is_exp ? nn : nullptr;
+    r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
+    TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
+
+    // 3. parallel kernel
+    TileArgs t;
+    t.X = q; t.Y = k; t.Z = v; t.Out = H;
+    t.wrow = w.wrow; t.wcol = w.ucol; t.srow = w.sH; t.St = w.stT;
+    t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
+    t.variant = variant; t.eps = eps; t.nstate = w.nst; t.mout = mout; t.nout = is_exp ? n_out : nullptr;
+    t.dotwith = nullptr; t.dotpart = nullptr; t.E = nullptr;
+    TFLA_LAUNCH(K_TILE_H, launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
+
+    if (!is_exp) {
+        if (nn) TFLA_LAUNCH(K_FILL, launch_fill_zero(nn, d.BH * dqk, s));
+        if (mn) TFLA_LAUNCH(K_FILL, launch_fill_zero(mn, d.BH, s));
+        if (n_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(n_out, d.BHT, s));
+        if (m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(m_out, d.BHT, s));
+    }
+    return TFLA_OK;
+}
+
+
+int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
+             const float* n0, const float* m0, const float* n_out, const float* m_out, const void* dH, const float* dCn,
+             int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype, float eps, float softcap, void* dq,
+             void* dk, void* dv, float* d_i_pre, float* d_f_pre, float* dC0, const void* fwd_workspace,
+             size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (rc != TFLA_OK) return rc;
+    if (!q || !k || !v || !i_pre || !f_pre || !dH || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
+    const bool is_exp = variant == TFLA_EXP;
+    if (is_exp) {
+        if (!n_out || !m_out) return TFLA_ERR_NULL;
+        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
+        if (given != 0 && given != 3) return TFLA_ERR_STATE;
+    }
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+    const BwdWs w = carve_bwd(d, workspace);
+    if (workspace_bytes < w.bytes) return TFLA_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    // What the matching forward call left in its workspace (gate vectors, C_{k-1} for every chunk,
+    // C_T) is reused when the caller hands that workspace over; otherwise it is recomputed here.
+    FwdWs fw{};
+    const bool reuse = fwd_workspace != nullptr;
+    if (reuse) {
+        if ((reinterpret_cast<uintptr_t>(fwd_workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+        fw = carve_fwd(d, const_cast<void*>(fwd_workspace));
+        if (fwd_workspace_bytes < fw.bytes) return TFLA_ERR_WORKSPACE;
+    }
+    // the generic fp32 kernels read the states of dQ / dK as (d_qk, d_hv); the bf16 kernels read
+    // (d_hv, d_qk) everywhere, so only that layout is ever written on the bf16 path
+    const bool tonly = dtype == TFLA_BF16;
+    const bool reuse_states = reuse && tonly;
+    const float* wrow = reuse ? fw.wrow : w.wrow;
+    const float* ucol = reuse ? fw.ucol : w.ucol;
+    const float* sH = reuse ? fw.sH : w.sH;
+    const float* aK = reuse ? fw.aK : w.aK;
+    const float* gbar = reuse ? fw.gbar : w.gbar;
+
+    // 1. gates as in the forward pass, then fold 1/h_denom into the backward weights
+    if (!reuse) {
+        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, softcap, s);
+        if (st != TFLA_OK) return st;
+    }
+    GateBwdPrepArgs p;
+    p.wrow = wrow; p.sH = sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
+    p.n = d.BHT; p.variant = variant; p.eps = eps;
+    TFLA_LAUNCH(K_BWD_PREP, launch_gate_bwd_prep(p, s));
+
+    // 2. the chunk states C_{k-1}
+    const void* cstates = reuse_states ? fw.stT : w.cN;
+    const float* Cfinal = reuse_states ? fw.Cfin : w.Cfinal;
+    if (!reuse_states) {
+        RecArgs r;
+        r.X = k; r.Y = v; r.rs = aK; r.gbar = gbar; r.S0 = C0;
+        r.stT = tonly ? w.cN : nullptr; r.stN = tonly ? nullptr : w.cN;
+        r.Sfinal = dCn ? w.Cfinal : nullptr; r.Sfinal2 = nullptr;
+        r.n0 = nullptr; r.nst = nullptr; r.nfinal = nullptr;
+        r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
+        TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
+    }
+
+    // 3. backward recurrence: dC_k for every chunk, dC_0 at the end
+    RecArgs rb;
+    rb.X = q; rb.Y = dH; rb.rs = w.sQ; rb.gbar = gbar; rb.S0 = dCn;
+    rb.stT = w.dcT; rb.stN = tonly ? nullptr : w.dcN; rb.Sfinal = dC0; rb.Sfinal2 = nullptr;
+    rb.n0 = nullptr; rb.nst = nullptr; rb.nfinal = nullptr;
+    rb.T = T; rb.L = chunk; rb.Nc = d.Nc; rb.d1 = dqk; rb.d2 = dhv; rb.reverse = 1;
+    TFLA_LAUNCH(K_REC_BWD, launch_recurrent(rb, (int)d.BH, dtype, s));
+
+    // 4. the three gradient kernels
+    TileArgs t;
+    t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
+    t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr; t.E = w.E;
+    // dV: rows = kv index j
+    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = w.dcT;
+    t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
+    TFLA_LAUNCH(K_TILE_DV, launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
+    // dQ: rows = query index i
+    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = w.wrowB; t.wcol = ucol; t.srow = w.sQ; t.St = cstates;
+    t.d1 = dhv; t.d2 = dqk; t.dotwith = q; t.dotpart = w.partQ;
+    TFLA_LAUNCH(K_TILE_DQ, launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
+    // dK: rows = kv index j
+    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = tonly ? w.dcT : w.dcN;
+    t.d1 = dhv; t.d2 = dqk; t.dotwith = k; t.dotpart = w.partK;
+    TFLA_LAUNCH(K_TILE_DK, launch_tile_mode<MODE_DK>(t, (int)d.BH, dtype, s));
+
+    // 5. gate gradients
+    if (dCn) TFLA_LAUNCH(K_STATE_DOT, launch_state_dot(Cfinal, dCn, w.cdot, (long)dqk * dhv, (int)d.BH, s));
+    GateGradArgs gg;
+    gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
+    gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
+    gg.BHT = d.BHT; gg.bsum = w.bsum; gg.softcap = softcap;
+    TFLA_LAUNCH(K_GATE_GRADS, launch_gate_grads(gg, (int)d.BH, s));
+    return TFLA_OK;
+}
+
 
 }  // namespace
 
@@ -247,49 +397,8 @@ int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_p
                    const float* C0, const float* n0, const float* m0, int B, int NH, int T, int dqk, int dhv,
                    int chunk, int variant, int dtype, float eps, void* H, float* Cn, float* nn, float* mn,
                    float* n_out, float* m_out, void* workspace, size_t workspace_bytes, void* stream) {
-    const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
-    if (rc != TFLA_OK) return rc;
-    if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
-    if (variant == TFLA_EXP) {
-        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
-        if (given != 0 && given != 3) return TFLA_ERR_STATE;
-    }
-    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
-    const FwdWs w = carve_fwd(d, workspace);
-    if (workspace_bytes < w.bytes) return TFLA_ERR_WORKSPACE;
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const bool is_exp = variant == TFLA_EXP;
-
-    // 1. gates, max states
-    float* mout = (is_exp && m_out) ? m_out : w.mout;
-    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, s);
-    if (st != TFLA_OK) return st;
-
-    // 2. recurrent kernel: C_{k-1} (transposed, element type of q/k/v) and n_{k-1} for every chunk
-    RecArgs r;
-    r.X = k; r.Y = v; r.rs = w.aK; r.gbar = w.gbar; r.S0 = C0;
-    r.stT = w.stT; r.stN = nullptr; r.Sfinal = Cn; r.Sfinal2 = w.Cfin;
-    r.n0 = is_exp ? n0 : nullptr; r.nst = is_exp ? w.nst : nullptr; r.nfinal = is_exp ? nn : nullptr;
-    r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
-    TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
-
-    // 3. parallel kernel
-    TileArgs t;
-    t.X = q; t.Y = k; t.Z = v; t.Out = H;
-    t.wrow = w.wrow; t.wcol = w.ucol; t.srow = w.sH; t.St = w.stT;
-    t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
-    t.variant = variant; t.eps = eps; t.nstate = w.nst; t.mout = mout; t.nout = is_exp ? n_out : nullptr;
-    t.dotwith = nullptr; t.dotpart = nullptr; t.E = nullptr;
-    TFLA_LAUNCH(K_TILE_H, launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
-
-    if (!is_exp) {
-        if (nn) TFLA_LAUNCH(K_FILL, launch_fill_zero(nn, d.BH * dqk, s));
-        if (mn) TFLA_LAUNCH(K_FILL, launch_fill_zero(mn, d.BH, s));
-        if (n_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(n_out, d.BHT, s));
-        if (m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(m_out, d.BHT, s));
-    }
-    return TFLA_OK;
+    return fwd_impl(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, dqk, dhv, chunk, variant, dtype, eps, 0.0f, H, Cn, nn,
+                    mn, n_out, m_out, workspace, workspace_bytes, stream);
 }
 
 int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
@@ -298,96 +407,9 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
                    int variant, int dtype, float eps, void* dq, void* dk, void* dv, float* d_i_pre,
                    float* d_f_pre, float* dC0, const void* fwd_workspace, size_t fwd_workspace_bytes,
                    void* workspace, size_t workspace_bytes, void* stream) {
-    const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
-    if (rc != TFLA_OK) return rc;
-    if (!q || !k || !v || !i_pre || !f_pre || !dH || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
-    const bool is_exp = variant == TFLA_EXP;
-    if (is_exp) {
-        if (!n_out || !m_out) return TFLA_ERR_NULL;
-        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
-        if (given != 0 && given != 3) return TFLA_ERR_STATE;
-    }
-    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
-    const BwdWs w = carve_bwd(d, workspace);
-    if (workspace_bytes < w.bytes) return TFLA_ERR_WORKSPACE;
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-
-    // What the matching forward call left in its workspace (gate vectors, C_{k-1} for every chunk,
-    // C_T) is reused when the caller hands that workspace over; otherwise it is recomputed here.
-    FwdWs fw{};
-    const bool reuse = fwd_workspace != nullptr;
-    if (reuse) {
-        if ((reinterpret_cast<uintptr_t>(fwd_workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
-        fw = carve_fwd(d, const_cast<void*>(fwd_workspace));
-        if (fwd_workspace_bytes < fw.bytes) return TFLA_ERR_WORKSPACE;
-    }
-    // the generic fp32 kernels read the states of dQ / dK as (d_qk, d_hv); the bf16 kernels read
-    // (d_hv, d_qk) everywhere, so only that layout is ever written on the bf16 path
-    const bool tonly = dtype == TFLA_BF16;
-    const bool reuse_states = reuse && tonly;
-    const float* wrow = reuse ? fw.wrow : w.wrow;
-    const float* ucol = reuse ? fw.ucol : w.ucol;
-    const float* sH = reuse ? fw.sH : w.sH;
-    const float* aK = reuse ? fw.aK : w.aK;
-    const float* gbar = reuse ? fw.gbar : w.gbar;
-
-    // 1. gates as in the forward pass, then fold 1/h_denom into the backward weights
-    if (!reuse) {
-        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, s);
-        if (st != TFLA_OK) return st;
-    }
-    GateBwdPrepArgs p;
-    p.wrow = wrow; p.sH = sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
-    p.n = d.BHT; p.variant = variant; p.eps = eps;
-    TFLA_LAUNCH(K_BWD_PREP, launch_gate_bwd_prep(p, s));
-
-    // 2. the chunk states C_{k-1}
-    const void* cstates = reuse_states ? fw.stT : w.cN;
-    const float* Cfinal = reuse_states ? fw.Cfin : w.Cfinal;
-    if (!reuse_states) {
-        RecArgs r;
-        r.X = k; r.Y = v; r.rs = aK; r.gbar = gbar; r.S0 = C0;
-        r.stT = tonly ? w.cN : nullptr; r.stN = tonly ? nullptr : w.cN;
-        r.Sfinal = dCn ? w.Cfinal : nullptr; r.Sfinal2 = nullptr;
-        r.n0 = nullptr; r.nst = nullptr; r.nfinal = nullptr;
-        r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
-        TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
-    }
-
-    // 3. backward recurrence: dC_k for every chunk, dC_0 at the end
-    RecArgs rb;
-    rb.X = q; rb.Y = dH; rb.rs = w.sQ; rb.gbar = gbar; rb.S0 = dCn;
-    rb.stT = w.dcT; rb.stN = tonly ? nullptr : w.dcN; rb.Sfinal = dC0; rb.Sfinal2 = nullptr;
-    rb.n0 = nullptr; rb.nst = nullptr; rb.nfinal = nullptr;
-    rb.T = T; rb.L = chunk; rb.Nc = d.Nc; rb.d1 = dqk; rb.d2 = dhv; rb.reverse = 1;
-    TFLA_LAUNCH(K_REC_BWD, launch_recurrent(rb, (int)d.BH, dtype, s));
-
-    // 4. the three gradient kernels
-    TileArgs t;
-    t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
-    t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr; t.E = w.E;
-    // dV: rows = kv index j
-    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = w.dcT;
-    t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
-    TFLA_LAUNCH(K_TILE_DV, launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
-    // dQ: rows = query index i
-    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = w.wrowB; t.wcol = ucol; t.srow = w.sQ; t.St = cstates;
-    t.d1 = dhv; t.d2 = dqk; t.dotwith = q; t.dotpart = w.partQ;
-    TFLA_LAUNCH(K_TILE_DQ, launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
-    // dK: rows = kv index j
-    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = tonly ? w.dcT : w.dcN;
-    t.d1 = dhv; t.d2 = dqk; t.dotwith = k; t.dotpart = w.partK;
-    TFLA_LAUNCH(K_TILE_DK, launch_tile_mode<MODE_DK>(t, (int)d.BH, dtype, s));
-
-    // 5. gate gradients
-    if (dCn) TFLA_LAUNCH(K_STATE_DOT, launch_state_dot(Cfinal, dCn, w.cdot, (long)dqk * dhv, (int)d.BH, s));
-    GateGradArgs gg;
-    gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
-    gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
-    gg.BHT = d.BHT; gg.bsum = w.bsum;
-    TFLA_LAUNCH(K_GATE_GRADS, launch_gate_grads(gg, (int)d.BH, s));
-    return TFLA_OK;
+    return bwd_impl(q, k, v, i_pre, f_pre, C0, n0, m0, n_out, m_out, dH, dCn, B, NH, T, dqk, dhv, chunk, variant, dtype,
+                    eps, 0.0f, dq, dk, dv, d_i_pre, d_f_pre, dC0, fwd_workspace, fwd_workspace_bytes, workspace,
+                    workspace_bytes, stream);
 }
 
 int tfla_mlstm_step(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
@@ -408,12 +430,105 @@ int tfla_mlstm_step(const void* q, const void* k, const void* v, const float* i_
     a.q = q; a.k = k; a.v = v; a.i_pre = i_pre; a.f_pre = f_pre;
     a.C = C; a.n = variant == TFLA_EXP ? n : nullptr; a.m = variant == TFLA_EXP ? m : nullptr;
     a.C_out = C_out; a.n_out = variant == TFLA_EXP ? n_out : nullptr; a.m_out = variant == TFLA_EXP ? m_out : nullptr;
-    a.h = h; a.dqk = dqk; a.dhv = dhv; a.variant = variant; a.dtype = dtype; a.eps = eps;
+    a.h = h; a.dqk = dqk; a.dhv = dhv; a.variant = variant; a.dtype = dtype; a.eps = eps; a.softcap = 0.0f;
     TFLA_LAUNCH(K_STEP, launch_step(a, B * NH, s));
     if (variant == TFLA_SIG) {
         if (n_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(n_out, (long)B * NH * dqk, s));
         if (m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(m_out, (long)B * NH, s));
     }
+    return TFLA_OK;
+}
+
+size_t tfla_mlstm_layer_workspace_bytes(int direction, int B, int NH, int T, int dqk, int dhv, int chunk, int variant,
+                                        int dtype) {
+    const size_t base = tfla_mlstm_workspace_bytes(direction, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (base == 0 || direction == TFLA_FWD) return base;
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    return base + align_up((size_t)d.BHT * dhv * d.esz) + align_up((size_t)d.BH * norm_row_blocks(T) * 2 * dhv * sizeof(float));
+}
+
+int tfla_mlstm_layer_fwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                         const void* o_pre, const float* gamma, const float* beta, const float* C0, const float* n0,
+                         const float* m0, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype,
+                         float eps, float gate_softcap, int norm_kind, float norm_eps, void* Y, void* H, float* Cn,
+                         float* nn, float* mn, float* n_out, float* m_out, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+    if (norm_kind != TFLA_NORM_RMS && norm_kind != TFLA_NORM_LAYER) return TFLA_ERR_ENUM;
+    if (!(gate_softcap >= 0.0f) || !(norm_eps >= 0.0f)) return TFLA_ERR_SHAPE;
+    if (!Y) return TFLA_ERR_NULL;
+    const int rc = fwd_impl(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, dqk, dhv, chunk, variant, dtype, eps,
+                            gate_softcap, H, Cn, nn, mn, n_out, m_out, workspace, workspace_bytes, stream);
+    if (rc != TFLA_OK) return rc;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    NormArgs a;
+    a.h = H; a.o_pre = o_pre; a.gamma = gamma; a.beta = beta; a.y = Y;
+    a.rows = (long)B * NH * T; a.NH = NH; a.T = T; a.d = dhv; a.kind = norm_kind; a.dtype = dtype; a.eps = norm_eps;
+    TFLA_LAUNCH(K_NORM_FWD, launch_norm_gate_fwd(a, s));
+    return TFLA_OK;
+}
+
+int tfla_mlstm_layer_bwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                         const void* o_pre, const float* gamma, const float* beta, const float* C0, const float* n0,
+                         const float* m0, const void* H, const float* n_out, const float* m_out, const void* dY,
+                         const float* dCn, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype,
+                         float eps, float gate_softcap, int norm_kind, float norm_eps, void* dq, void* dk, void* dv,
+                         float* d_i_pre, float* d_f_pre, void* do_pre, float* dgamma, float* dbeta, float* dC0,
+                         const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (rc != TFLA_OK) return rc;
+    if (norm_kind != TFLA_NORM_RMS && norm_kind != TFLA_NORM_LAYER) return TFLA_ERR_ENUM;
+    if (!(gate_softcap >= 0.0f) || !(norm_eps >= 0.0f)) return TFLA_ERR_SHAPE;
+    if (!q || !k || !v || !i_pre || !f_pre || !H || !dY || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
+    if (variant == TFLA_EXP) {
+        if (!n_out || !m_out) return TFLA_ERR_NULL;
+        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
+        if (given != 0 && given != 3) return TFLA_ERR_STATE;
+    }
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+    if (fwd_workspace && ((reinterpret_cast<uintptr_t>(fwd_workspace) & 255) != 0 ||
+                          fwd_workspace_bytes < carve_fwd(d, nullptr).bytes))
+        return TFLA_ERR_WORKSPACE;
+    const size_t base = carve_bwd(d, nullptr).bytes;
+    const int nblk = norm_row_blocks(T);
+    Carver c(reinterpret_cast<char*>(workspace) + base);
+    void* dHt = c.take_bytes((size_t)d.BHT * dhv * d.esz);
+    float* part = c.take<float>((size_t)d.BH * nblk * 2 * dhv);
+    if (workspace_bytes < base + c.off) return TFLA_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    // NORM + output gate backward: dY -> d h~ (the cell's upstream gradient), d o~, parameter sums
+    const bool want_params = dgamma != nullptr || (dbeta != nullptr && norm_kind == TFLA_NORM_LAYER);
+    NormBwdArgs a;
+    a.h = H; a.o_pre = o_pre; a.gamma = gamma; a.beta = beta; a.dy = dY; a.dh = dHt; a.do_pre = do_pre;
+    a.part = want_params ? part : nullptr;
+    a.NH = NH; a.T = T; a.d = dhv; a.kind = norm_kind; a.dtype = dtype; a.eps = norm_eps;
+    TFLA_LAUNCH(K_NORM_BWD, launch_norm_gate_bwd(a, (int)d.BH, s));
+    if (want_params) {
+        NormParamGradArgs pg;
+        pg.part = part; pg.dgamma = dgamma; pg.dbeta = norm_kind == TFLA_NORM_LAYER ? dbeta : nullptr;
+        pg.B = B; pg.NH = NH; pg.nblk = nblk; pg.d = dhv;
+        TFLA_LAUNCH(K_NORM_BWD, launch_norm_param_grad(pg, s));
+    }
+    if (dbeta && norm_kind != TFLA_NORM_LAYER) TFLA_LAUNCH(K_FILL, launch_fill_zero(dbeta, (long)NH * dhv, s));
+    return bwd_impl(q, k, v, i_pre, f_pre, C0, n0, m0, n_out, m_out, dHt, dCn, B, NH, T, dqk, dhv, chunk, variant, dtype,
+                    eps, gate_softcap, dq, dk, dv, d_i_pre, d_f_pre, dC0, fwd_workspace, fwd_workspace_bytes, workspace,
+                    base, stream);
+}
+
+int tfla_transfer_gain(const void* h, const void* v, int B, int NH, int T, int dhv, int dtype, int norm_kind,
+                       float norm_eps, float* g_before, float* g_after, void* stream) {
+    if (dtype != TFLA_F32 && dtype != TFLA_BF16) return TFLA_ERR_ENUM;
+    if (norm_kind != TFLA_NORM_RMS && norm_kind != TFLA_NORM_LAYER) return TFLA_ERR_ENUM;
+    if (B <= 0 || NH <= 0 || T <= 0 || dhv <= 0 || dhv % 8 != 0 || dhv > 2048 || (long)B * NH > 2147483647L) return TFLA_ERR_SHAPE;
+    if (!(norm_eps >= 0.0f)) return TFLA_ERR_SHAPE;
+    if (!h || !v || !g_before || !g_after) return TFLA_ERR_NULL;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    GainArgs a;
+    a.h = h; a.v = v; a.g_before = g_before; a.g_after = g_after; a.T = T; a.d = dhv; a.kind = norm_kind; a.dtype = dtype;
+    a.eps = norm_eps;
+    TFLA_LAUNCH(K_GAIN, launch_transfer_gain(a, B * NH, s));
     return TFLA_OK;
 }
 

@@ -9,6 +9,13 @@ namespace tfla {
 static constexpr float LOG2E = 1.4426950408889634f;
 
 __device__ __forceinline__ float log_sigmoid(float x) { return fminf(x, 0.0f) - log1pf(expf(-fabsf(x))); }
+// gate soft-cap c tanh(x / c) (App. E, soft-capping equation); c = 0 leaves x as it is
+__device__ __forceinline__ float soft_cap(float x, float c) { return c > 0.0f ? c * tanhf(x / c) : x; }
+__device__ __forceinline__ float soft_cap_grad(float x, float c) {
+    if (!(c > 0.0f)) return 1.0f;
+    const float t = tanhf(x / c);
+    return 1.0f - t * t;
+}
 __device__ __forceinline__ float sigmoid_neg(float x) {  // sigma(-x), no overflow
     const float e = expf(-fabsf(x));
     return x >= 0.0f ? e / (1.0f + e) : 1.0f / (1.0f + e);
@@ -64,14 +71,14 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a
     float* ta = tc + a.T;
     const long t0 = (long)kc * a.L + (long)lane * E;
     float fsum = 0.0f;
-    for (int e = 0; e < E; ++e) fsum += log_sigmoid(a.f_pre[row + t0 + e]);
+    for (int e = 0; e < E; ++e) fsum += log_sigmoid(soft_cap(a.f_pre[row + t0 + e], a.softcap));
     const float off = wave_excl_scan_add(fsum, lane);
     const float roff = wave_excl_rscan_add(fsum, lane);
     // forward pass: b, u = i-bar - b, running max of u
     float b = off, cmx = -INFINITY;
     for (int e = 0; e < E; ++e) {
-        const float fb = log_sigmoid(a.f_pre[row + t0 + e]);
-        const float ip = a.i_pre[row + t0 + e];
+        const float fb = log_sigmoid(soft_cap(a.f_pre[row + t0 + e], a.softcap));
+        const float ip = soft_cap(a.i_pre[row + t0 + e], a.softcap);
         const float ib = is_exp ? ip : log_sigmoid(ip);
         b += fb;
         cmx = fmaxf(cmx, ib - b);
@@ -79,8 +86,8 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a
     const float cmoff = wave_excl_scan_max(cmx, lane);
     b = off; cmx = cmoff;
     for (int e = 0; e < E; ++e) {
-        const float fb = log_sigmoid(a.f_pre[row + t0 + e]);
-        const float ip = a.i_pre[row + t0 + e];
+        const float fb = log_sigmoid(soft_cap(a.f_pre[row + t0 + e], a.softcap));
+        const float ip = soft_cap(a.i_pre[row + t0 + e], a.softcap);
         const float ib = is_exp ? ip : log_sigmoid(ip);
         b += fb;
         const float u = ib - b;
@@ -92,12 +99,12 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a
     // reverse pass: a_j = sum_{s>j} f-bar_s + i-bar_j
     float run = roff, amax = -INFINITY;
     for (int e = E - 1; e >= 0; --e) {
-        const float ip = a.i_pre[row + t0 + e];
+        const float ip = soft_cap(a.i_pre[row + t0 + e], a.softcap);
         const float ib = is_exp ? ip : log_sigmoid(ip);
         const float av = run + ib;
         ta[t0 + e] = av;
         amax = fmaxf(amax, av);
-        run += log_sigmoid(a.f_pre[row + t0 + e]);
+        run += log_sigmoid(soft_cap(a.f_pre[row + t0 + e], a.softcap));
     }
     amax = wave_max(amax);
     const float gsum = wave_sum(fsum);
@@ -274,8 +281,9 @@ __global__ void __launch_bounds__(256) gate_grads_kernel(GateGradArgs a) {
         const int t = t0 + e;
         if (t < a.T) {
             run += (double)r[e] - (double)c[e];
-            a.d_f[row + t] = (float)run * sigmoid_neg(a.f_pre[row + t]);
-            a.d_i[row + t] = a.variant == 0 ? c[e] : c[e] * sigmoid_neg(a.i_pre[row + t]);
+            const float fp = a.f_pre[row + t], ip = a.i_pre[row + t];
+            a.d_f[row + t] = (float)run * sigmoid_neg(soft_cap(fp, a.softcap)) * soft_cap_grad(fp, a.softcap);
+            a.d_i[row + t] = (a.variant == 0 ? c[e] : c[e] * sigmoid_neg(soft_cap(ip, a.softcap))) * soft_cap_grad(ip, a.softcap);
         }
     }
 }

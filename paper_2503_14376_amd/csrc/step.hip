@@ -25,7 +25,8 @@ __global__ void __launch_bounds__(256) step_kernel(StepArgs a) {
     const DT* q = reinterpret_cast<const DT*>(a.q) + (long)bh * dqk;
     const DT* k = reinterpret_cast<const DT*>(a.k) + (long)bh * dqk;
     const DT* v = reinterpret_cast<const DT*>(a.v) + (long)bh * dhv + nb * 64;
-    const float ip = a.i_pre[bh], fp = a.f_pre[bh];
+    float ip = a.i_pre[bh], fp = a.f_pre[bh];
+    if (a.softcap > 0.0f) { ip = a.softcap * tanhf(ip / a.softcap); fp = a.softcap * tanhf(fp / a.softcap); }
     const float qscale = 1.0f / sqrtf((float)dqk);
     // gates (Sec. 2.1: m_t = max(log sigma(f~) + m_{t-1}, i~), stabilised f', i'; Sec. 4.1: sigmoids)
     float fg, ig, m_new = 0.0f;

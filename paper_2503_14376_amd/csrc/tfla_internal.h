@@ -13,6 +13,7 @@ struct GateArgs {
     const float* m0;      // (BH) or NULL
     int T, L, Nc, variant;
     float qscale;         // 1/sqrt(dqk)
+    float softcap;        // c of the gate soft-cap c tanh(x / c) on both pre-activations; 0 = none
     // outputs, all (BH, T) unless noted
     float* wrow;          // log2-domain row term of the intra-chunk weight (includes log2 qscale)
     float* ucol;          // log2-domain column term (i-bar_j - b_j) * log2(e)
@@ -41,6 +42,7 @@ struct GateGradArgs {
     float* d_i; float* d_f;
     double* bsum;                  // (BH, ceil(T / 1024)) scratch: block sums
     int T, variant; long BHT;
+    float softcap;                 // as in GateArgs: the gradients are taken through the cap
 };
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
 
@@ -56,8 +58,45 @@ struct StepArgs {
     void* h;                                       // (BH, dhv)
     int dqk, dhv, variant, dtype;
     float eps;
+    float softcap;                                 // gate soft-cap, 0 = none
 };
 hipError_t launch_step(const StepArgs& a, int BH, hipStream_t s);
+
+// ---- NORM + output gate around the cell (Sec. 2.1 output equation; Sec. 4.1 RMS norm), transfer gains ----
+struct NormArgs {
+    const void* h;        // (rows, d) cell output h~, element type per dtype
+    const void* o_pre;    // (rows, d) output gate pre-activations, or NULL (gate = 1)
+    const float* gamma;   // (NH, d) or NULL (1)
+    const float* beta;    // (NH, d) or NULL (0); LayerNorm only
+    void* y;              // (rows, d)
+    long rows;            // B * NH * T, row = (b * NH + head) * T + t
+    int NH, T, d, kind, dtype;   // kind 0 = RMS norm, 1 = LayerNorm
+    float eps;
+};
+hipError_t launch_norm_gate_fwd(const NormArgs& a, hipStream_t s);
+struct NormBwdArgs {
+    const void* h; const void* o_pre; const float* gamma; const float* beta;
+    const void* dy;       // (rows, d)
+    void* dh;             // (rows, d)
+    void* do_pre;         // (rows, d) or NULL
+    float* part;          // (BH, row blocks, 2, d) partial sums for d gamma / d beta, or NULL
+    int NH, T, d, kind, dtype;
+    float eps;
+};
+hipError_t launch_norm_gate_bwd(const NormBwdArgs& a, int BH, hipStream_t s);
+int norm_row_blocks(int T);
+struct NormParamGradArgs {
+    const float* part; float* dgamma; float* dbeta;   // outputs (NH, d), either may be NULL
+    int B, NH, nblk, d;
+};
+hipError_t launch_norm_param_grad(const NormParamGradArgs& a, hipStream_t s);
+struct GainArgs {
+    const void* h; const void* v;   // (BH, T, d)
+    float* g_before; float* g_after;   // (BH)
+    int T, d, kind, dtype;
+    float eps;
+};
+hipError_t launch_transfer_gain(const GainArgs& a, int BH, hipStream_t s);
 
 // ---- inter-chunk recurrence (App. B.2 "Inter-chunk Recurrent Contribution"; App. B.3) -------
 // state <- gbar[k] * state + (rs (.) X_k)^T Y_k, chunk by chunk; the state *before* each

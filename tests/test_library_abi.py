@@ -165,3 +165,58 @@ def test_step_argument_validation_happens_before_any_launch(tfla):
     assert call(n=2, m=0) == -6                    # state only partly given
     assert call(n=4, n_out=4) == -6                # n_out must not alias n
     assert call(m=5, m_out=5) == -6
+
+
+def test_layer_argument_validation_happens_before_any_launch(tfla):
+    lib = tfla.load_library()
+    P = lambda x: ctypes.c_void_p(x * 4096) if x else None
+    a = OK_ARGS
+    cf = ctypes.c_float
+
+    def fwd(Y=1, H=1, q=1, norm=0, cap=15.0, neps=1e-6, ws=1, ws_bytes=1 << 40, chunk=256):
+        return lib.tfla_mlstm_layer_fwd(P(q), P(1), P(1), P(1), P(1), P(1), P(1), None, None, None, None,
+                                        a["B"], a["NH"], a["T"], a["dqk"], a["dhv"], chunk, a["variant"], a["dtype"],
+                                        cf(1e-6), cf(cap), norm, cf(neps), P(Y), P(H), None, None, None, None, None,
+                                        P(ws), ws_bytes, None)
+    assert fwd(Y=0) == -1
+    assert fwd(H=0) == -1
+    assert fwd(q=0) == -1
+    assert fwd(norm=7) == -4
+    assert fwd(cap=-1.0) == -2
+    assert fwd(neps=-1.0) == -2
+    assert fwd(chunk=100) == -3
+    assert fwd(ws=0) == -5
+    assert fwd(ws_bytes=1024) == -5
+
+    def bwd(H=1, dY=1, dq=1, n_out=1, norm=1, ws=1, ws_bytes=1 << 40, fws=0, fws_bytes=0):
+        return lib.tfla_mlstm_layer_bwd(P(1), P(1), P(1), P(1), P(1), P(1), P(1), P(1), None, None, None,
+                                        P(H), P(n_out), P(1), P(dY), None,
+                                        a["B"], a["NH"], a["T"], a["dqk"], a["dhv"], a["chunk"], a["variant"], a["dtype"],
+                                        cf(1e-6), cf(15.0), norm, cf(1e-6), P(dq), P(1), P(1), P(1), P(1), P(1), P(1), P(1),
+                                        None, P(fws), fws_bytes, P(ws), ws_bytes, None)
+    assert bwd(H=0) == -1
+    assert bwd(dY=0) == -1
+    assert bwd(dq=0) == -1
+    assert bwd(n_out=0) == -1
+    assert bwd(norm=-1) == -4
+    assert bwd(ws=0) == -5
+    # the layer's backward workspace is larger than the cell's: the cell's size alone is refused
+    args9 = (a["B"], a["NH"], a["T"], a["dqk"], a["dhv"], a["chunk"], a["variant"], a["dtype"])
+    cell = lib.tfla_mlstm_workspace_bytes(1, *args9)
+    layer = lib.tfla_mlstm_layer_workspace_bytes(1, *args9)
+    assert layer >= cell + a["B"] * a["NH"] * a["T"] * a["dhv"] * 2
+    assert lib.tfla_mlstm_layer_workspace_bytes(0, *args9) == lib.tfla_mlstm_workspace_bytes(0, *args9)
+    assert bwd(ws_bytes=cell) == -5
+    assert bwd(fws=1, fws_bytes=1024) == -5
+    assert lib.tfla_mlstm_layer_workspace_bytes(1, a["B"], a["NH"], a["T"], 100, a["dhv"], a["chunk"], 0, 1) == 0
+
+    def gain(h=1, gb=1, dhv=128, dtype=1, norm=0, neps=1e-6, T=512):
+        return lib.tfla_transfer_gain(P(h), P(1), 2, 3, T, dhv, dtype, norm, cf(neps), P(gb), P(1), None)
+    assert gain(h=0) == -1
+    assert gain(gb=0) == -1
+    assert gain(dhv=100) == -2
+    assert gain(dhv=4096) == -2
+    assert gain(T=0) == -2
+    assert gain(dtype=3) == -4
+    assert gain(norm=2) == -4
+    assert gain(neps=-1.0) == -2

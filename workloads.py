@@ -113,6 +113,36 @@ def make_inputs(w: Workload, heads: Optional[int] = None) -> Dict[str, np.ndarra
     return d
 
 
+def make_layer_inputs(w: Workload, heads: Optional[int] = None, gate_scale: float = 1.0) -> Dict[str, np.ndarray]:
+    """The inputs of make_inputs plus what the layer around the cell reads: output-gate
+    pre-activations o_pre ~ N(0,1) shaped like v, norm scale gamma ~ 1 + N(0, std 0.1) and shift
+    beta ~ N(0, std 0.1) per head, an upstream gradient dY ~ N(0,1) (stored under "dH" by
+    make_inputs).  gate_scale multiplies both gate pre-activations (to reach the range where a
+    soft-cap matters).  With `heads`, the first `heads` slices must belong to one batch element."""
+    d = make_inputs(w, heads)
+    BH = w.B * w.NH
+    n = BH if heads is None else min(heads, BH)
+    assert heads is None or n <= w.NH
+    shp = (w.B, w.NH) if heads is None else (1, n)
+    o = np.empty((n, w.T, w.dhv), dtype=np.float32)
+    for s in range(n):
+        g = np.random.Generator(np.random.Philox(key=w.seed, counter=[9, s, 0, 0]))
+        o[s] = g.standard_normal((w.T, w.dhv), dtype=np.float32)
+    o = o.reshape(shp + (w.T, w.dhv))
+    d["o_pre"] = bf16_round(o) if w.dtype == BF16 else o
+    nh = w.NH if heads is None else n
+    gam = np.empty((nh, w.dhv), dtype=np.float32); bet = np.empty((nh, w.dhv), dtype=np.float32)
+    for h in range(nh):
+        g = np.random.Generator(np.random.Philox(key=w.seed, counter=[10, h, 0, 0]))
+        gam[h] = np.float32(1.0) + np.float32(0.1) * g.standard_normal((w.dhv,), dtype=np.float32)
+        bet[h] = np.float32(0.1) * g.standard_normal((w.dhv,), dtype=np.float32)
+    d["gamma"] = gam; d["beta"] = bet
+    if gate_scale != 1.0:
+        d["i_pre"] = (d["i_pre"] * np.float32(gate_scale)).astype(np.float32)
+        d["f_pre"] = (d["f_pre"] * np.float32(gate_scale)).astype(np.float32)
+    return d
+
+
 def small(variant: int, dtype: int, B=1, NH=2, T=256, dqk=64, dhv=128, chunk=64,
           seed=7, init_state=True, backward=True, f_mean=3.0) -> Workload:
     """A reduced workload of the same recipe for parity tests."""
