@@ -38,7 +38,7 @@ def rel_err(gpu, ref):
     return float(np.max(np.abs(g - ref)) / max(np.max(np.abs(ref)), 1e-30))
 
 
-def check_fwd(w, d, out, ref, tol=None, state=True, report=None):
+def check_fwd(w, d, out, ref, tol=None, state=True, report=None, abs_tol=1e-4):
     tol = TOL[w.dtype] if tol is None else tol
     errs = {"H": rel_err(out["H"], ref["H"])}
     if state:
@@ -54,6 +54,6 @@ def check_fwd(w, d, out, ref, tol=None, state=True, report=None):
     if report is not None:
         report.update(errs)
     for key, e in errs.items():
-        lim = 1e-4 if key.endswith("_abs") else tol
+        lim = abs_tol if key.endswith("_abs") else tol
         assert e <= lim, (w.name, key, e, errs)
     return errs

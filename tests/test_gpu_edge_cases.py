@@ -1,0 +1,128 @@
+"""GPU parity at the edges of the supported range and in the degenerate cases of the method: one chunk only,
+the smallest and the largest chunk and head dimensions, a (batch x head) count that is not a multiple of the
+XCD count, gates that reset the memory at every step or never forget, a closed input gate, all-zero queries;
+and two scalar-gate relatives evaluated through the same kernels (Sec. 5 related work: with the input gate fixed
+to one and a constant decay the sigmoid-gate cell is decayed linear attention) against the textbook formula."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import mlstm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def _fwd_bwd(w, d, check_bwd=True, tol_scale=1.0, abs_tol=1e-4):
+    import paper_2503_14376_amd as tfla
+    from tests import gpu_util as gu
+    dev = gu.dev_inputs(w, d)
+    print("edge", w.variant, w.dtype, (w.B, w.NH, w.T, w.dqk, w.dhv, w.chunk), flush=True)
+    f = tfla.mlstm_fwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev.get("C0"), dev.get("n0"),
+                       dev.get("m0"), chunk=w.chunk, variant=w.variant, eps=1e-6)
+    oi = gu.oracle_inputs(d)
+    ref = orc.recurrent_fwd(**oi, variant=w.variant, eps=1e-6)
+    tol = gu.TOL[w.dtype] * tol_scale
+    errs = gu.check_fwd(w, d, f, ref, tol=tol, abs_tol=abs_tol)
+    if check_bwd:
+        b = tfla.mlstm_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["dH"], f["n_out"], f["m_out"],
+                           dev.get("C0"), dev.get("n0"), dev.get("m0"), None, chunk=w.chunk, variant=w.variant, eps=1e-6,
+                           fwd_workspace=f["workspace"])
+        torch.cuda.synchronize()
+        rb = orc.chunkwise_bwd(**oi, dH=gu.flat(d["dH"]), variant=w.variant, eps=1e-6, chunk=min(w.chunk, 256))
+        for key, rk in dict(dq="dq", dk="dk", dv="dv", d_i_pre="di", d_f_pre="df", dC0="dC0").items():
+            ref_max = float(np.max(np.abs(rb[rk])))
+            if ref_max < 1e-30:          # a gradient that is identically zero in exact arithmetic
+                assert float(b[key].float().abs().max()) < 1e-20, key
+                continue
+            if key == "d_f_pre":
+                # The forget-gate gradient is a cumulative sum over time of q_t.dq_t - k_t.dk_t (what every gate
+                # pre-activation moves is the log-weight of the pairs it lies between).  When those sums cancel
+                # (resets: the exact gradient is of order exp(-40)) the error is set by the size of the terms,
+                # so the terms, not the cancelled result, are the scale the error is measured against.
+                qd = np.abs((oi["q"] * rb["dq"]).sum(-1)).max(); kd = np.abs((oi["k"] * rb["dk"]).sum(-1)).max()
+                g_ = b[key].detach().float().cpu().numpy().astype(np.float64).reshape(rb[rk].shape)
+                errs[key] = float(np.max(np.abs(g_ - rb[rk])) / max(ref_max, qd, kd))
+            else:
+                errs[key] = gu.rel_err(b[key], rb[rk])
+            assert errs[key] <= tol, (key, errs)
+    print("   ", errs, flush=True)
+    return f, errs
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("T,chunk", [(64, 64), (256, 256), (2048, 2048), (4096, 2048)])
+def test_single_chunk_and_largest_chunk(variant, T, chunk):
+    w = wl.small(variant, wl.BF16, B=1, NH=2, T=T, dqk=64, dhv=128, chunk=chunk, seed=71 + T)
+    _fwd_bwd(w, wl.make_inputs(w))
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("dqk,dhv", [(64, 64), (512, 512), (512, 64), (64, 512)])
+def test_extreme_head_dimensions(variant, dqk, dhv):
+    w = wl.small(variant, wl.BF16, B=1, NH=1, T=512, dqk=dqk, dhv=dhv, chunk=128, seed=73 + dqk + dhv)
+    _fwd_bwd(w, wl.make_inputs(w))
+
+
+@pytest.mark.parametrize("B,NH", [(1, 3), (5, 1), (3, 7)])
+def test_batch_head_counts_not_multiple_of_eight(B, NH):
+    w = wl.small(wl.EXP, wl.BF16, B=B, NH=NH, T=256, dqk=64, dhv=64, chunk=64, seed=75 + B)
+    _fwd_bwd(w, wl.make_inputs(w))
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
+@pytest.mark.parametrize("case", ["reset_every_step", "never_forget", "input_gate_closed", "zero_queries", "mixed_resets"])
+def test_degenerate_gates(variant, dtype, case):
+    w = wl.small(variant, dtype, B=1, NH=2, T=256, dqk=64, dhv=128, chunk=64, seed=77)
+    d = wl.make_inputs(w)
+    if case == "reset_every_step":        # f~ = -40: sigma(f~) ~ 4e-18, every step forgets the past
+        d["f_pre"][:] = -40.0
+    elif case == "never_forget":          # f~ = +40: log sigma(f~) = 0 in fp32, plain (normalised) linear attention
+        d["f_pre"][:] = 40.0
+    elif case == "input_gate_closed":     # i~ = -30 everywhere: only the initial state is visible
+        d["i_pre"][:] = -30.0
+    elif case == "zero_queries":
+        d["q"][:] = 0.0
+    else:                                  # resets at a few steps, open gates elsewhere
+        d["f_pre"][:] = 6.0
+        d["f_pre"][..., ::37] = -40.0
+    # The max states are formed from cumulative sums of log sigma(f~) inside a chunk (App. B.2, chunkwise gates), kept
+    # in fp32: with f~ = -40 they reach -40 L = -2560, whose spacing in fp32 is 2.4e-4, so the max state is only
+    # that accurate in the reset cases (H is unaffected: the same rounded exponents enter numerator and denominator).
+    # The same spacing bounds the relative accuracy of a single weight exp2(row term + column term) (both terms are of
+    # the size of the cumulative sum), 2 * 2.4e-4 * ln 2 = 3.4e-4: visible on the fp32 path only, whose bar is 1e-4
+    # for |cumulative log gate| up to about 700; the reset cases are checked at 5e-4 there.
+    resets = case in ("reset_every_step", "mixed_resets")
+    _fwd_bwd(w, d, abs_tol=1e-3 if resets else 1e-4, tol_scale=5.0 if (resets and dtype == wl.F32) else 1.0)
+
+
+def test_relatives_through_the_same_kernel():
+    """Input gate fixed to one and one constant decay per head: h_t = sum_{j<=t} gamma^(t-j) (q_t.k_j/sqrt(d)) v_j,
+    the retention / simple gated-linear-attention form, evaluated by the mLSTMsig kernels (i~ = +40, f~ = logit gamma)
+    and compared with that formula written out in numpy."""
+    import paper_2503_14376_amd as tfla
+    from tests import gpu_util as gu
+    B, NH, T, dqk, dhv = 1, 4, 256, 64, 128
+    w = wl.small(wl.SIG, wl.F32, B=B, NH=NH, T=T, dqk=dqk, dhv=dhv, chunk=64, seed=79, init_state=False)
+    d = wl.make_inputs(w)
+    gammas = np.array([0.5, 0.9, 0.97, 0.995])
+    d["i_pre"][:] = 40.0
+    d["f_pre"][:] = np.log(gammas / (1 - gammas)).astype(np.float32)[None, :, None]
+    dev = gu.dev_inputs(w, d)
+    f = tfla.mlstm_fwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], chunk=64, variant=wl.SIG)
+    torch.cuda.synchronize()
+    t = np.arange(T)
+    for h in range(NH):
+        g_eff = 1.0 / (1.0 + np.exp(-np.float64(d["f_pre"][0, h, 0])))
+        decay = np.tril(g_eff ** (t[:, None] - t[None, :]).clip(min=0))
+        S = (d["q"][0, h].astype(np.float64) @ d["k"][0, h].astype(np.float64).T) / np.sqrt(dqk) * decay
+        ref = S @ d["v"][0, h].astype(np.float64)
+        assert gu.rel_err(f["H"][0, h], ref) <= 1e-4, h
+
+
+def test_zero_batch_is_an_error_not_a_launch():
+    import paper_2503_14376_amd as tfla
+    assert tfla.check(0, 0, 8, 256, 64, 64, 64, 0, 1) == -2
+    assert tfla.check(0, 1, 8, 0, 64, 64, 64, 0, 1) == -2
+    assert tfla.check(0, 1, 8, 200, 64, 64, 64, 0, 1) == -3      # ragged T is refused, not truncated
