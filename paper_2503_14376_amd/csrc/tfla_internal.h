@@ -141,11 +141,11 @@ struct TileArgs {
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
 // d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16
-// wavefront within 256 registers, so that two workgroups share a CU when d1 <= 256.  The bf16 dK
-// kernel, which computes no S of its own, takes a 256-wide block when d1 = 512 (one workgroup per
-// CU anyway): half as many workgroups fetch the same X rows and E tiles.
+// wavefront within 256 registers, so that two workgroups share a CU when d1 <= 256.  The bf16 dQ and
+// dK kernels take a 256-wide block when d1 = 512 (one workgroup per CU anyway): half as many
+// workgroups fetch the same X rows and column tiles, and dQ computes S once per 256 columns.
 inline int tile_bd2(int d1, int d2, int dtype, int mode) {
-    if (dtype == 1 && mode == MODE_DK && d1 == 512 && d2 % 256 == 0) return 256;
+    if (dtype == 1 && (mode == MODE_DK || mode == MODE_DQ) && d1 == 512 && d2 % 256 == 0) return 256;
     if (d2 % 128 == 0) return 128;
     return 64;
 }

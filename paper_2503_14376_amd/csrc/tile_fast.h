@@ -300,7 +300,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         const int cs = ct * BC;
         const bool masked = UPPER ? (cs + 31 < wr0) : (cs > wr0 + 31);   // fully masked for this wave
         // with one wavefront per SIMD the request is spread between the matrix instructions below
-        constexpr bool SPREAD = false;   // measured slower: the groups lose the read-ahead across their boundaries
+        // with 128-column blocks measured slower (the groups lose the read-ahead across their boundaries); with
+        // 256-column blocks it keeps the Y fragments of a tile within the register budget
+        constexpr bool SPREAD = !ELITE && BD2 == 256 && D1 == 512;
         if (req && (!SPREAD || masked)) issue(i + NS - 1);
         if (masked) continue;
         const bool diag = UPPER ? (cs < wr0 + 31) : (cs + 31 > wr0);
