@@ -26,9 +26,13 @@
  *  - variant TFLA_SIG has no normaliser and no max state: n0, m0 and eps are ignored and
  *    nn, mn, n_out, m_out are filled with zeros when non-NULL.
  *  - eps is added to the denominator max{|n^T q~|, exp(-m)}; eps = 0 is the paper's formula.
- *  - Restrictions: T % chunk == 0, chunk % 64 == 0, 64 <= chunk <= 2048,
- *    T / chunk <= 4096, dqk and dhv in {64, 128, 256, 512} (at most 256 for TFLA_F32),
+ *  - Restrictions: chunk % 64 == 0, 64 <= chunk <= 2048, ceil(T / chunk) <= 4096, dqk and dhv in {64, 128, 256, 512} (at most 256 for TFLA_F32),
  *    B * NH <= 65535.
+ *  - T need not be a multiple of chunk (N_c = ceil(T / chunk), Sec. 2.2).  The kernels work on whole
+ *    chunks: for such a T the library copies the inputs into zero-padded buffers inside the workspace
+ *    (which is correspondingly larger, see tfla_mlstm_workspace_bytes), gives the padding steps a forget
+ *    gate of one and an input gate of zero, and copies the first T steps of the results back, so the
+ *    result is that of the T-step sequence; tensor pointers must then be 16-byte aligned (TFLA_ERR_SHAPE).
  *  - Return value: TFLA_OK (0) on success; a negative TFLA_ERR_* code for an invalid
  *    argument (checked before anything is launched, nothing is written); a positive value is
  *    the hipError_t of a failed launch.  No entry point throws or aborts.
@@ -57,7 +61,7 @@ enum {
     TFLA_OK = 0,
     TFLA_ERR_NULL = -1,        /* a required pointer is NULL                                 */
     TFLA_ERR_SHAPE = -2,       /* a dimension is non-positive or violates the restrictions   */
-    TFLA_ERR_CHUNK = -3,       /* chunk does not divide T or is not an allowed chunk size    */
+    TFLA_ERR_CHUNK = -3,       /* not an allowed chunk size, or too many chunks              */
     TFLA_ERR_ENUM = -4,        /* unknown variant / dtype / direction                        */
     TFLA_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned (256 B) or too small            */
     TFLA_ERR_STATE = -6        /* C0/n0/m0 (or Cn/nn/mn) only partly given                   */

@@ -12,7 +12,7 @@ namespace {
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Dims {
-    int B, NH, T, dqk, dhv, L, variant, dtype;
+    int B, NH, T, dqk, dhv, L, variant, dtype;   // T: whole chunks (the padded length when the caller's is ragged)
     long BH, BHT;
     int Nc;
     size_t esz;
@@ -27,16 +27,18 @@ int check_dims(int direction, int B, int NH, int T, int dqk, int dhv, int chunk,
     auto ok_d = [&](int d) { return (d == 64 || d == 128 || d == 256 || d == 512) && d <= dmax; };
     if (!ok_d(dqk) || !ok_d(dhv)) return TFLA_ERR_SHAPE;
     if ((long)B * NH > 65535) return TFLA_ERR_SHAPE;
-    if (chunk < 64 || chunk > 2048 || chunk % 64 != 0 || T % chunk != 0) return TFLA_ERR_CHUNK;
-    if (T / chunk > 4096) return TFLA_ERR_CHUNK;
-    if ((long)B * NH * (T / chunk) > 2147483647L / 2) return TFLA_ERR_SHAPE;
+    if (chunk < 64 || chunk > 2048 || chunk % 64 != 0) return TFLA_ERR_CHUNK;
+    const int nc = (T + chunk - 1) / chunk;
+    if (nc > 4096) return TFLA_ERR_CHUNK;
+    if ((long)B * NH * nc > 2147483647L / 2) return TFLA_ERR_SHAPE;
     return TFLA_OK;
 }
 
 Dims make_dims(int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype) {
     Dims d;
-    d.B = B; d.NH = NH; d.T = T; d.dqk = dqk; d.dhv = dhv; d.L = chunk; d.variant = variant; d.dtype = dtype;
-    d.BH = (long)B * NH; d.BHT = d.BH * T; d.Nc = T / chunk;
+    d.Nc = (T + chunk - 1) / chunk;
+    d.B = B; d.NH = NH; d.T = d.Nc * chunk; d.dqk = dqk; d.dhv = dhv; d.L = chunk; d.variant = variant; d.dtype = dtype;
+    d.BH = (long)B * NH; d.BHT = d.BH * d.T;
     d.esz = dtype == TFLA_BF16 ? 2 : 4;
     return d;
 }
@@ -118,10 +120,10 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
 
 // ---- optional per-kernel timing with HIP events on the caller's stream -------------------
 enum { K_GATES = 0, K_BWD_PREP, K_REC_FWD, K_REC_BWD, K_TILE_H, K_TILE_DV, K_TILE_DQ, K_TILE_DK, K_GATE_GRADS,
-       K_STATE_DOT, K_FILL, K_STEP, K_NORM_FWD, K_NORM_BWD, K_GAIN, K_COUNT };
+       K_STATE_DOT, K_FILL, K_STEP, K_NORM_FWD, K_NORM_BWD, K_GAIN, K_PAD, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"gates", "gate_bwd_prep", "recurrent_fwd", "recurrent_bwd", "tile_H",
                                            "tile_dV", "tile_dQ", "tile_dK", "gate_grads", "state_dot", "fill_zero",
-                                           "recurrent_step", "norm_gate_fwd", "norm_gate_bwd", "transfer_gain"};
+                                           "recurrent_step", "norm_gate_fwd", "norm_gate_bwd", "transfer_gain", "pad_copy"};
 struct Profiler {
     bool on = false;
     int cap = 0, used = 0;
@@ -167,9 +169,9 @@ void prof_collect() {
 
 int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float* m0, float* wrow, float* ucol,
               float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, float* csum, float softcap,
-              hipStream_t s) {
+              int Tvalid, hipStream_t s) {
     GateArgs g;
-    g.softcap = softcap;
+    g.softcap = softcap; g.Tvalid = Tvalid;
     g.i_pre = i_pre; g.f_pre = f_pre; g.m0 = d.variant == TFLA_EXP ? m0 : nullptr;
     g.T = d.T; g.L = d.L; g.Nc = d.Nc; g.variant = d.variant;
     g.qscale = 1.0f / sqrtf((float)d.dqk);
@@ -178,9 +180,10 @@ int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float
     return TFLA_OK;
 }
 
-int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
-             const float* n0, const float* m0, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype,
-             float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
+// Forward pass over whole chunks: T is a multiple of chunk, steps >= Tvalid are padding.
+int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
+             const float* n0, const float* m0, int B, int NH, int T, int Tvalid, int dqk, int dhv, int chunk, int variant,
+             int dtype, float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
              void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
     if (rc != TFLA_OK) return rc;
@@ -198,7 +201,7 @@ int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
 
     // 1. gates, max states
     float* mout = (is_exp && m_out) ? m_out : w.mout;
-    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, softcap, s);
+    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, softcap, Tvalid, s);
     if (st != TFLA_OK) return st;
 
     // 2. recurrent kernel: C_{k-1} (transposed, element type of q/k/v) and n_{k-1} for every chunk
@@ -228,9 +231,9 @@ int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
 }
 
 
-int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
+int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
              const float* n0, const float* m0, const float* n_out, const float* m_out, const void* dH, const float* dCn,
-             int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype, float eps, float softcap, void* dq,
+             int B, int NH, int T, int Tvalid, int dqk, int dhv, int chunk, int variant, int dtype, float eps, float softcap, void* dq,
              void* dk, void* dv, float* d_i_pre, float* d_f_pre, float* dC0, const void* fwd_workspace,
              size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
@@ -269,7 +272,7 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
 
     // 1. gates as in the forward pass, then fold 1/h_denom into the backward weights
     if (!reuse) {
-        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, softcap, s);
+        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, softcap, Tvalid, s);
         if (st != TFLA_OK) return st;
     }
     GateBwdPrepArgs p;
@@ -326,6 +329,131 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
 }
 
 
+// ---- sequence lengths that do not fill the last chunk -------------------------------------------
+// The cores work on whole chunks.  For a ragged T the entry points copy the inputs into buffers of
+// Nc * chunk steps behind the core's own workspace (zero rows past T), run the core there with
+// Tvalid = T, and copy the first T steps of the per-step outputs back.
+struct PadFwd { void *q, *k, *v, *H; float *ip, *fp, *nout, *mout; size_t bytes; };
+PadFwd carve_pad_fwd(const Dims& d, void* base) {
+    Carver c(base);
+    PadFwd p;
+    p.q = c.take_bytes((size_t)d.BHT * d.dqk * d.esz); p.k = c.take_bytes((size_t)d.BHT * d.dqk * d.esz);
+    p.v = c.take_bytes((size_t)d.BHT * d.dhv * d.esz); p.H = c.take_bytes((size_t)d.BHT * d.dhv * d.esz);
+    p.ip = c.take<float>(d.BHT); p.fp = c.take<float>(d.BHT); p.nout = c.take<float>(d.BHT); p.mout = c.take<float>(d.BHT);
+    p.bytes = c.off;
+    return p;
+}
+struct PadBwd { void *q, *k, *v, *dH, *dq, *dk, *dv; float *ip, *fp, *nout, *mout, *di, *df; size_t bytes; };
+PadBwd carve_pad_bwd(const Dims& d, void* base) {
+    Carver c(base);
+    PadBwd p;
+    const size_t sq = (size_t)d.BHT * d.dqk * d.esz, sv = (size_t)d.BHT * d.dhv * d.esz;
+    p.q = c.take_bytes(sq); p.k = c.take_bytes(sq); p.v = c.take_bytes(sv); p.dH = c.take_bytes(sv);
+    p.dq = c.take_bytes(sq); p.dk = c.take_bytes(sq); p.dv = c.take_bytes(sv);
+    p.ip = c.take<float>(d.BHT); p.fp = c.take<float>(d.BHT); p.nout = c.take<float>(d.BHT); p.mout = c.take<float>(d.BHT);
+    p.di = c.take<float>(d.BHT); p.df = c.take<float>(d.BHT);
+    p.bytes = c.off;
+    return p;
+}
+size_t fwd_total_bytes(const Dims& d, int T) {
+    return carve_fwd(d, nullptr).bytes + (T == d.T ? 0 : carve_pad_fwd(d, nullptr).bytes);
+}
+size_t bwd_total_bytes(const Dims& d, int T) {
+    return carve_bwd(d, nullptr).bytes + (T == d.T ? 0 : carve_pad_bwd(d, nullptr).bytes);
+}
+inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
+             const float* n0, const float* m0, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype,
+             float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
+             void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (rc != TFLA_OK) return rc;
+    if (T % chunk == 0)
+        return fwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, T, dqk, dhv, chunk, variant, dtype, eps, softcap, H, Cn,
+                        nn, mn, n_out, m_out, workspace, workspace_bytes, stream);
+    if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
+    if (variant == TFLA_EXP) {
+        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
+        if (given != 0 && given != 3) return TFLA_ERR_STATE;
+    }
+    if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(H)) return TFLA_ERR_SHAPE;
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+    const size_t core_bytes = carve_fwd(d, nullptr).bytes;
+    const PadFwd p = carve_pad_fwd(d, reinterpret_cast<char*>(workspace) + core_bytes);
+    if (workspace_bytes < core_bytes + p.bytes) return TFLA_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const int Tp = d.T;
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, dqk * (int)d.esz, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, dqk * (int)d.esz, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, dhv * (int)d.esz, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
+    const int st = fwd_core(p.q, p.k, p.v, p.ip, p.fp, C0, n0, m0, B, NH, Tp, T, dqk, dhv, chunk, variant, dtype, eps,
+                            softcap, p.H, Cn, nn, mn, n_out ? p.nout : nullptr, m_out ? p.mout : nullptr, workspace,
+                            core_bytes, stream);
+    if (st != TFLA_OK) return st;
+    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.H, H, d.BH, T, Tp, dhv * (int)d.esz, s));
+    if (n_out) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.nout, n_out, d.BH, T, Tp, s));
+    if (m_out) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.mout, m_out, d.BH, T, Tp, s));
+    return TFLA_OK;
+}
+
+int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
+             const float* n0, const float* m0, const float* n_out, const float* m_out, const void* dH, const float* dCn,
+             int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype, float eps, float softcap, void* dq,
+             void* dk, void* dv, float* d_i_pre, float* d_f_pre, float* dC0, const void* fwd_workspace,
+             size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (rc != TFLA_OK) return rc;
+    if (T % chunk == 0)
+        return bwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, n_out, m_out, dH, dCn, B, NH, T, T, dqk, dhv, chunk, variant,
+                        dtype, eps, softcap, dq, dk, dv, d_i_pre, d_f_pre, dC0, fwd_workspace, fwd_workspace_bytes,
+                        workspace, workspace_bytes, stream);
+    if (!q || !k || !v || !i_pre || !f_pre || !dH || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
+    const bool is_exp = variant == TFLA_EXP;
+    if (is_exp) {
+        if (!n_out || !m_out) return TFLA_ERR_NULL;
+        const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
+        if (given != 0 && given != 3) return TFLA_ERR_STATE;
+    }
+    if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(dH) || misaligned16(dq) || misaligned16(dk) ||
+        misaligned16(dv))
+        return TFLA_ERR_SHAPE;
+    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
+    if (fwd_workspace && ((reinterpret_cast<uintptr_t>(fwd_workspace) & 255) != 0 ||
+                          fwd_workspace_bytes < carve_fwd(d, nullptr).bytes))
+        return TFLA_ERR_WORKSPACE;
+    const size_t core_bytes = carve_bwd(d, nullptr).bytes;
+    const PadBwd p = carve_pad_bwd(d, reinterpret_cast<char*>(workspace) + core_bytes);
+    if (workspace_bytes < core_bytes + p.bytes) return TFLA_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const int Tp = d.T, eq = dqk * (int)d.esz, ev = dhv * (int)d.esz;
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, eq, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, eq, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, ev, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(dH, p.dH, d.BH, T, Tp, ev, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
+    if (is_exp) {
+        // denominators of the padding steps: max{|1|, exp(0)} -- any finite non-zero value would do
+        TFLA_LAUNCH(K_PAD, launch_pad_scalar(n_out, p.nout, d.BH, T, Tp, 1.0f, s));
+        TFLA_LAUNCH(K_PAD, launch_pad_scalar(m_out, p.mout, d.BH, T, Tp, 0.0f, s));
+    }
+    const int st = bwd_core(p.q, p.k, p.v, p.ip, p.fp, C0, n0, m0, is_exp ? p.nout : nullptr, is_exp ? p.mout : nullptr,
+                            p.dH, dCn, B, NH, Tp, T, dqk, dhv, chunk, variant, dtype, eps, softcap, p.dq, p.dk, p.dv, p.di,
+                            p.df, dC0, fwd_workspace, fwd_workspace_bytes, workspace, core_bytes, stream);
+    if (st != TFLA_OK) return st;
+    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dq, dq, d.BH, T, Tp, eq, s));
+    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dk, dk, d.BH, T, Tp, eq, s));
+    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dv, dv, d.BH, T, Tp, ev, s));
+    TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.di, d_i_pre, d.BH, T, Tp, s));
+    TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.df, d_f_pre, d.BH, T, Tp, s));
+    return TFLA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -372,7 +500,7 @@ const char* tfla_status_string(int status) {
         case TFLA_OK: return "ok";
         case TFLA_ERR_NULL: return "a required pointer is NULL";
         case TFLA_ERR_SHAPE: return "invalid or unsupported dimension";
-        case TFLA_ERR_CHUNK: return "chunk must be a multiple of 64 in [64, 2048] that divides T (T/chunk <= 4096)";
+        case TFLA_ERR_CHUNK: return "chunk must be a multiple of 64 in [64, 2048] with at most 4096 chunks per sequence";
         case TFLA_ERR_ENUM: return "unknown variant, dtype or direction";
         case TFLA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
         case TFLA_ERR_STATE: return "state must be given completely (C, n, m) or not at all; n_out/m_out must not alias n/m";
@@ -390,7 +518,7 @@ size_t tfla_mlstm_workspace_bytes(int direction, int B, int NH, int T, int dqk, 
                                   int dtype) {
     if (check_dims(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) != TFLA_OK) return 0;
     const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
-    return direction == TFLA_FWD ? carve_fwd(d, nullptr).bytes : carve_bwd(d, nullptr).bytes;
+    return direction == TFLA_FWD ? fwd_total_bytes(d, T) : bwd_total_bytes(d, T);
 }
 
 int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
@@ -444,7 +572,7 @@ size_t tfla_mlstm_layer_workspace_bytes(int direction, int B, int NH, int T, int
     const size_t base = tfla_mlstm_workspace_bytes(direction, B, NH, T, dqk, dhv, chunk, variant, dtype);
     if (base == 0 || direction == TFLA_FWD) return base;
     const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
-    return base + align_up((size_t)d.BHT * dhv * d.esz) + align_up((size_t)d.BH * norm_row_blocks(T) * 2 * dhv * sizeof(float));
+    return base + align_up((size_t)d.BH * T * dhv * d.esz) + align_up((size_t)d.BH * norm_row_blocks(T) * 2 * dhv * sizeof(float));
 }
 
 int tfla_mlstm_layer_fwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
@@ -490,10 +618,10 @@ int tfla_mlstm_layer_bwd(const void* q, const void* k, const void* v, const floa
     if (fwd_workspace && ((reinterpret_cast<uintptr_t>(fwd_workspace) & 255) != 0 ||
                           fwd_workspace_bytes < carve_fwd(d, nullptr).bytes))
         return TFLA_ERR_WORKSPACE;
-    const size_t base = carve_bwd(d, nullptr).bytes;
+    const size_t base = bwd_total_bytes(d, T);
     const int nblk = norm_row_blocks(T);
     Carver c(reinterpret_cast<char*>(workspace) + base);
-    void* dHt = c.take_bytes((size_t)d.BHT * dhv * d.esz);
+    void* dHt = c.take_bytes((size_t)d.BH * T * dhv * d.esz);
     float* part = c.take<float>((size_t)d.BH * nblk * 2 * dhv);
     if (workspace_bytes < base + c.off) return TFLA_ERR_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);

@@ -70,25 +70,31 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a
     float* tc = tb + a.T;
     float* ta = tc + a.T;
     const long t0 = (long)kc * a.L + (long)lane * E;
+    // log gates of step t; the padding steps of a sequence that does not fill its last chunk keep the
+    // state as it is (log forget gate 0) and add nothing (log input gate far below every other)
+    auto fbar = [&](long t) { return t < a.Tvalid ? log_sigmoid(soft_cap(a.f_pre[row + t], a.softcap)) : 0.0f; };
+    auto ibar = [&](long t) {
+        if (t >= a.Tvalid) return -1.0e30f;
+        const float ip = soft_cap(a.i_pre[row + t], a.softcap);
+        return is_exp ? ip : log_sigmoid(ip);
+    };
     float fsum = 0.0f;
-    for (int e = 0; e < E; ++e) fsum += log_sigmoid(soft_cap(a.f_pre[row + t0 + e], a.softcap));
+    for (int e = 0; e < E; ++e) fsum += fbar(t0 + e);
     const float off = wave_excl_scan_add(fsum, lane);
     const float roff = wave_excl_rscan_add(fsum, lane);
     // forward pass: b, u = i-bar - b, running max of u
     float b = off, cmx = -INFINITY;
     for (int e = 0; e < E; ++e) {
-        const float fb = log_sigmoid(soft_cap(a.f_pre[row + t0 + e], a.softcap));
-        const float ip = soft_cap(a.i_pre[row + t0 + e], a.softcap);
-        const float ib = is_exp ? ip : log_sigmoid(ip);
+        const float fb = fbar(t0 + e);
+        const float ib = ibar(t0 + e);
         b += fb;
         cmx = fmaxf(cmx, ib - b);
     }
     const float cmoff = wave_excl_scan_max(cmx, lane);
     b = off; cmx = cmoff;
     for (int e = 0; e < E; ++e) {
-        const float fb = log_sigmoid(soft_cap(a.f_pre[row + t0 + e], a.softcap));
-        const float ip = soft_cap(a.i_pre[row + t0 + e], a.softcap);
-        const float ib = is_exp ? ip : log_sigmoid(ip);
+        const float fb = fbar(t0 + e);
+        const float ib = ibar(t0 + e);
         b += fb;
         const float u = ib - b;
         cmx = fmaxf(cmx, u);
@@ -99,12 +105,10 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a
     // reverse pass: a_j = sum_{s>j} f-bar_s + i-bar_j
     float run = roff, amax = -INFINITY;
     for (int e = E - 1; e >= 0; --e) {
-        const float ip = soft_cap(a.i_pre[row + t0 + e], a.softcap);
-        const float ib = is_exp ? ip : log_sigmoid(ip);
-        const float av = run + ib;
+        const float av = run + ibar(t0 + e);
         ta[t0 + e] = av;
         amax = fmaxf(amax, av);
-        run += log_sigmoid(soft_cap(a.f_pre[row + t0 + e], a.softcap));
+        run += fbar(t0 + e);
     }
     amax = wave_max(amax);
     const float gsum = wave_sum(fsum);

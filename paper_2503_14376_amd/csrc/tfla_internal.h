@@ -12,6 +12,7 @@ struct GateArgs {
     const float* f_pre;   // (BH, T)
     const float* m0;      // (BH) or NULL
     int T, L, Nc, variant;
+    int Tvalid;           // steps t >= Tvalid of every (batch, head) are padding: forget gate 1, input gate 0
     float qscale;         // 1/sqrt(dqk)
     float softcap;        // c of the gate soft-cap c tanh(x / c) on both pre-activations; 0 = none
     // outputs, all (BH, T) unless noted
@@ -47,6 +48,12 @@ struct GateGradArgs {
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
 
 hipError_t launch_fill_zero(float* p, long n, hipStream_t s);
+// (BH, T, row) <-> (BH, Tp, row) copies for sequence lengths that are not a multiple of the chunk (pad.hip);
+// row_bytes a multiple of 16, pointers 16-byte aligned
+hipError_t launch_pad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, hipStream_t s);
+hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, hipStream_t s);
+hipError_t launch_pad_scalar(const float* in, float* out, long BH, int T, int Tp, float fill, hipStream_t s);
+hipError_t launch_unpad_scalar(const float* in, float* out, long BH, int T, int Tp, hipStream_t s);
 hipError_t launch_state_dot(const float* A, const float* Bm, float* out, long per, int BH, hipStream_t s);
 
 // ---- single recurrent step (Sec. 2.1, Sec. 4.1) ------------------------------------------------

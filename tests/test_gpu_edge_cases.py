@@ -121,8 +121,43 @@ def test_relatives_through_the_same_kernel():
         assert gu.rel_err(f["H"][0, h], ref) <= 1e-4, h
 
 
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
+@pytest.mark.parametrize("T,chunk", [(1, 64), (63, 64), (100, 64), (200, 64), (449, 128), (1000, 256)])
+def test_ragged_sequence_length(variant, dtype, T, chunk):
+    """T is not a multiple of the chunk (N_c = ceil(T / L), Sec. 2.2): outputs, final state and all gradients are those
+    of the T-step sequence (the oracle's recurrence and its ragged last chunk know nothing of padding)."""
+    import paper_2503_14376_amd as tfla
+    from tests import gpu_util as gu
+    w = wl.small(variant, dtype, B=2, NH=2, T=T, dqk=64, dhv=128, chunk=chunk, seed=81 + T)
+    d = wl.make_inputs(w)
+    f, _ = _fwd_bwd(w, d, check_bwd=T > 1)
+    if T >= 100:
+        # continuation: the returned state is the state after step T, not after the padded chunk
+        T1 = T - 37
+        cut = lambda a, lo, hi: np.ascontiguousarray(a[:, :, lo:hi])
+        dev = gu.dev_inputs(w, d)
+        sl = lambda key, lo, hi: dev[key][:, :, lo:hi].contiguous()
+        a = tfla.mlstm_fwd(sl("q", 0, T1), sl("k", 0, T1), sl("v", 0, T1), sl("i_pre", 0, T1), sl("f_pre", 0, T1),
+                           dev.get("C0"), dev.get("n0"), dev.get("m0"), chunk=chunk, variant=variant, eps=1e-6)
+        b = tfla.mlstm_fwd(sl("q", T1, T), sl("k", T1, T), sl("v", T1, T), sl("i_pre", T1, T), sl("f_pre", T1, T),
+                           a["Cn"], a["nn"] if variant == wl.EXP else None, a["mn"] if variant == wl.EXP else None,
+                           chunk=chunk, variant=variant, eps=1e-6)
+        torch.cuda.synchronize()
+        ref = orc.recurrent_fwd(**gu.oracle_inputs(d), variant=variant, eps=1e-6)
+        tol = gu.TOL[dtype]
+        assert gu.rel_err(b["H"], ref["H"][:, T1:].reshape(2, 2, T - T1, -1)) <= tol
+        assert gu.rel_err(b["Cn"], ref["Cn"]) <= tol
+
+
+def test_ragged_layer():
+    from tests.test_gpu_layer import run_layer
+    from oracle import layer_oracle as lo
+    w = wl.small(wl.EXP, wl.BF16, B=2, NH=2, T=300, dqk=64, dhv=128, chunk=128, seed=83, init_state=False)
+    run_layer(w, lo.LAYER, softcap=15.0, gate=True, gate_scale=2.0, chunk_oracle=50)
+
+
 def test_zero_batch_is_an_error_not_a_launch():
     import paper_2503_14376_amd as tfla
     assert tfla.check(0, 0, 8, 256, 64, 64, 64, 0, 1) == -2
     assert tfla.check(0, 1, 8, 0, 64, 64, 64, 0, 1) == -2
-    assert tfla.check(0, 1, 8, 200, 64, 64, 64, 0, 1) == -3      # ragged T is refused, not truncated

@@ -71,13 +71,24 @@ def test_check_accepts_the_benchmark_configurations(tfla):
     (dict(B=0), -2), (dict(NH=-1), -2), (dict(T=0), -2), (dict(dqk=96), -2), (dict(dhv=1024), -2),
     (dict(dtype=0, dhv=512), -2), (dict(B=4096, NH=16), -2),
     (dict(chunk=0), -3), (dict(chunk=32), -3), (dict(chunk=96), -3), (dict(chunk=4096), -3),
-    (dict(T=8192 + 64, chunk=256), -3), (dict(T=64 * 8192, chunk=64), -3),
+    (dict(T=64 * 8192, chunk=64), -3),
     (dict(variant=2), -4), (dict(dtype=7), -4), (dict(direction=3), -4),
 ])
 def test_check_rejects_invalid_dimensions(tfla, kw, code):
     assert _check(tfla, **kw) == code
     a = dict(OK_ARGS); a.update(kw)
     assert tfla.workspace_bytes(*[a[k] for k in ("direction", "B", "NH", "T", "dqk", "dhv", "chunk", "variant", "dtype")]) == 0
+
+
+def test_ragged_sequence_lengths_are_accepted_and_need_more_workspace(tfla):
+    assert _check(tfla, T=8192 + 64, chunk=256) == 0
+    assert _check(tfla, T=1, chunk=64) == 0
+    a = dict(OK_ARGS); a.pop("direction")
+    for direction in (0, 1):
+        whole = tfla.workspace_bytes(direction, **a)
+        ragged = tfla.workspace_bytes(direction, **dict(a, T=8192 - 1))
+        # the same number of chunks plus padded copies of the inputs and per-step outputs
+        assert ragged > whole + 16 * 8192 * (256 + 256 + 512) * 2
 
 
 def test_status_strings(tfla):
