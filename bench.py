@@ -162,6 +162,9 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--variant", default="")
     ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--head-dim", type=int, default=0,
+                    help="head-dimension sweep point of App. E.3: dqk = dhv = this value, NH = 4096 / value, B = 4 "
+                         "(unless --batch), T = 8192; a secondary line")
     ap.add_argument("--fwd-only", action="store_true")
     ap.add_argument("--recompute", action="store_true",
                     help="do not hand the forward workspace to the backward call (gates and chunk states are recomputed)")
@@ -198,6 +201,9 @@ def main() -> int:
         w = dataclasses.replace(w, chunk=args.chunk)
     if args.variant:
         w = dataclasses.replace(w, variant=wl.EXP if args.variant == "exp" else wl.SIG)
+    if args.head_dim:
+        w = dataclasses.replace(w, name="headdim%d" % args.head_dim, dqk=args.head_dim, dhv=args.head_dim,
+                                NH=4096 // args.head_dim, B=4, T=8192)
     if args.batch:
         w = dataclasses.replace(w, B=args.batch)
     do_bwd = not args.fwd_only
