@@ -202,6 +202,22 @@ TFLA_API int tfla_mlstm_layer_bwd(const void* q, const void* k, const void* v,
                          const void* fwd_workspace, size_t fwd_workspace_bytes,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * One generation step of the layer: tfla_mlstm_step with soft-capped gates, followed by the NORM and
+ * the output gate of tfla_mlstm_layer_fwd on the step's hidden state.
+ *   in : as tfla_mlstm_step, plus o_pre (B, NH, dhv) in `dtype` or NULL, gamma, beta (NH, dhv) float or NULL.
+ *   out: y (B, NH, dhv) in `dtype` (required); h: the cell output (required, also a scratch of the call);
+ *        C_out, n_out, m_out as in tfla_mlstm_step.
+ */
+TFLA_API int tfla_mlstm_layer_step(const void* q, const void* k, const void* v,
+                          const float* i_pre, const float* f_pre,
+                          const void* o_pre, const float* gamma, const float* beta,
+                          const float* C, const float* n, const float* m,
+                          int B, int NH, int dqk, int dhv,
+                          int variant, int dtype, float eps,
+                          float gate_softcap, int norm_kind, float norm_eps,
+                          void* y, void* h, float* C_out, float* n_out, float* m_out, void* stream);
+
 /* Workspace bytes of the two layer entry points (host function; 0 for invalid arguments). */
 TFLA_API size_t tfla_mlstm_layer_workspace_bytes(int direction, int B, int NH, int T, int dqk, int dhv,
                                         int chunk, int variant, int dtype);

@@ -17,7 +17,7 @@ _lib = None
 EXPORTS = ("tfla_mlstm_fwd", "tfla_mlstm_bwd", "tfla_mlstm_step", "tfla_mlstm_workspace_bytes", "tfla_mlstm_check",
            "tfla_status_string", "tfla_version", "tfla_profile_enable", "tfla_profile_read",
            "tfla_profile_kernels", "tfla_mlstm_layer_fwd", "tfla_mlstm_layer_bwd", "tfla_mlstm_layer_workspace_bytes",
-           "tfla_transfer_gain")
+           "tfla_transfer_gain", "tfla_mlstm_layer_step")
 
 
 class TflaError(RuntimeError):
@@ -57,6 +57,9 @@ def load_library():
                                          vp, vp, vp, fp, fp, vp, fp, fp, fp, vp, sz, vp, sz, vp]
     lib.tfla_mlstm_layer_workspace_bytes.restype = sz
     lib.tfla_mlstm_layer_workspace_bytes.argtypes = [ci] * 9
+    lib.tfla_mlstm_layer_step.restype = ci
+    lib.tfla_mlstm_layer_step.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, ci, ci, ci, ci, ci, ci, cf, cf, ci, cf,
+                                          vp, vp, fp, fp, fp, vp]
     lib.tfla_transfer_gain.restype = ci
     lib.tfla_transfer_gain.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, cf, fp, fp, vp]
     lib.tfla_mlstm_workspace_bytes.restype = sz
@@ -334,6 +337,40 @@ def mlstm_layer_bwd(q, k, v, i_pre, f_pre, H, dY, o_pre=None, gamma=None, beta=N
     return o
 
 
+def mlstm_layer_step(q, k, v, i_pre, f_pre, C, n=None, m=None, o_pre=None, gamma=None, beta=None, variant=EXP, eps=1e-6,
+                     gate_softcap=0.0, norm_kind=NORM_RMS, norm_eps=1e-6, stream=None, out: Optional[Dict] = None,
+                     inplace_C: bool = False) -> Dict:
+    """tfla_mlstm_layer_step on torch device tensors: mlstm_step with soft-capped gates, then norm and output gate.
+    o_pre: (B,NH,dhv) like v or None.  Returns y, h (cell output) and the new state C, n, m."""
+    import torch
+    lib = load_library()
+    B, NH, dqk = q.shape
+    dhv = v.shape[-1]
+    dtype = BF16 if q.dtype == torch.bfloat16 else F32
+    td, f32 = _torch_dtype(dtype), torch.float32
+    _want(q, td, (B, NH, dqk), "q"); _want(k, td, (B, NH, dqk), "k"); _want(v, td, (B, NH, dhv), "v")
+    _want(o_pre, td, (B, NH, dhv), "o_pre"); _want(gamma, f32, (NH, dhv), "gamma"); _want(beta, f32, (NH, dhv), "beta")
+    _want(i_pre, f32, (B, NH), "i_pre"); _want(f_pre, f32, (B, NH), "f_pre")
+    _want(C, f32, (B, NH, dqk, dhv), "C"); _want(n, f32, (B, NH, dqk), "n"); _want(m, f32, (B, NH), "m")
+    dev = q.device
+    o = out if out is not None else {}
+    if "y" not in o:
+        o["y"] = torch.empty((B, NH, dhv), dtype=td, device=dev)
+        o["h"] = torch.empty((B, NH, dhv), dtype=td, device=dev)
+    if "C" not in o:
+        o["C"] = C if inplace_C else torch.empty_like(C)
+    if "n" not in o:
+        o["n"] = torch.empty((B, NH, dqk), dtype=f32, device=dev)
+        o["m"] = torch.empty((B, NH), dtype=f32, device=dev)
+    rc = lib.tfla_mlstm_layer_step(_ptr(q), _ptr(k), _ptr(v), _ptr(i_pre), _ptr(f_pre), _ptr(o_pre), _ptr(gamma), _ptr(beta),
+                                   _ptr(C), _ptr(n), _ptr(m), B, NH, dqk, dhv, int(variant), dtype, float(eps),
+                                   float(gate_softcap), int(norm_kind), float(norm_eps), _ptr(o["y"]), _ptr(o["h"]),
+                                   _ptr(o["C"]), _ptr(o["n"]), _ptr(o["m"]), _stream_handle(stream))
+    if rc != 0:
+        raise TflaError(rc, "tfla_mlstm_layer_step")
+    return o
+
+
 def transfer_gain(h, v, norm_kind=NORM_RMS, norm_eps=1e-6, stream=None):
     """tfla_transfer_gain on torch device tensors h, v (B,NH,T,dhv).  Returns (g_before, g_after), each (B,NH) fp32."""
     import torch
@@ -347,5 +384,5 @@ def transfer_gain(h, v, norm_kind=NORM_RMS, norm_eps=1e-6, stream=None):
     rc = lib.tfla_transfer_gain(_ptr(h), _ptr(v), B, NH, T, dhv, dtype, int(norm_kind), float(norm_eps), _ptr(gb), _ptr(ga),
                                 _stream_handle(stream))
     if rc != 0:
-        raise TflaError(rc, "tfla_transfer_gain")
+        raise TflaError(rc, "tfla_transfer_gain", "tfla_mlstm_layer_step")
     return gb, ga

@@ -540,9 +540,10 @@ int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_p
                     workspace_bytes, stream);
 }
 
-int tfla_mlstm_step(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
-                    const float* C, const float* n, const float* m, int B, int NH, int dqk, int dhv, int variant,
-                    int dtype, float eps, void* h, float* C_out, float* n_out, float* m_out, void* stream) {
+static int step_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                     const float* C, const float* n, const float* m, int B, int NH, int dqk, int dhv, int variant,
+                     int dtype, float eps, float softcap, void* h, float* C_out, float* n_out, float* m_out,
+                     void* stream) {
     if (variant != TFLA_EXP && variant != TFLA_SIG) return TFLA_ERR_ENUM;
     if (dtype != TFLA_F32 && dtype != TFLA_BF16) return TFLA_ERR_ENUM;
     if (B <= 0 || NH <= 0 || (long)B * NH > 65535) return TFLA_ERR_SHAPE;
@@ -558,12 +559,38 @@ int tfla_mlstm_step(const void* q, const void* k, const void* v, const float* i_
     a.q = q; a.k = k; a.v = v; a.i_pre = i_pre; a.f_pre = f_pre;
     a.C = C; a.n = variant == TFLA_EXP ? n : nullptr; a.m = variant == TFLA_EXP ? m : nullptr;
     a.C_out = C_out; a.n_out = variant == TFLA_EXP ? n_out : nullptr; a.m_out = variant == TFLA_EXP ? m_out : nullptr;
-    a.h = h; a.dqk = dqk; a.dhv = dhv; a.variant = variant; a.dtype = dtype; a.eps = eps; a.softcap = 0.0f;
+    a.h = h; a.dqk = dqk; a.dhv = dhv; a.variant = variant; a.dtype = dtype; a.eps = eps; a.softcap = softcap;
     TFLA_LAUNCH(K_STEP, launch_step(a, B * NH, s));
     if (variant == TFLA_SIG) {
         if (n_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(n_out, (long)B * NH * dqk, s));
         if (m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(m_out, (long)B * NH, s));
     }
+    return TFLA_OK;
+}
+
+int tfla_mlstm_step(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                    const float* C, const float* n, const float* m, int B, int NH, int dqk, int dhv, int variant,
+                    int dtype, float eps, void* h, float* C_out, float* n_out, float* m_out, void* stream) {
+    return step_impl(q, k, v, i_pre, f_pre, C, n, m, B, NH, dqk, dhv, variant, dtype, eps, 0.0f, h, C_out, n_out, m_out,
+                     stream);
+}
+
+int tfla_mlstm_layer_step(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                          const void* o_pre, const float* gamma, const float* beta, const float* C, const float* n,
+                          const float* m, int B, int NH, int dqk, int dhv, int variant, int dtype, float eps,
+                          float gate_softcap, int norm_kind, float norm_eps, void* y, void* h, float* C_out,
+                          float* n_out, float* m_out, void* stream) {
+    if (norm_kind != TFLA_NORM_RMS && norm_kind != TFLA_NORM_LAYER) return TFLA_ERR_ENUM;
+    if (!(gate_softcap >= 0.0f) || !(norm_eps >= 0.0f)) return TFLA_ERR_SHAPE;
+    if (!y) return TFLA_ERR_NULL;
+    const int rc = step_impl(q, k, v, i_pre, f_pre, C, n, m, B, NH, dqk, dhv, variant, dtype, eps, gate_softcap, h, C_out,
+                             n_out, m_out, stream);
+    if (rc != TFLA_OK) return rc;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    NormArgs a;
+    a.h = h; a.o_pre = o_pre; a.gamma = gamma; a.beta = beta; a.y = y;
+    a.rows = (long)B * NH; a.NH = NH; a.T = 1; a.d = dhv; a.kind = norm_kind; a.dtype = dtype; a.eps = norm_eps;
+    TFLA_LAUNCH(K_NORM_FWD, launch_norm_gate_fwd(a, s));
     return TFLA_OK;
 }
 

@@ -144,3 +144,33 @@ def test_transfer_experiment_grid():
         assert np.all(res[variant][0] < 0.15) and np.all(np.abs(res[variant][-2:] - 1.0) < 0.5)
         assert np.all(np.diff(res[variant], axis=0) > -1e-3)      # the gain grows with the input gate
     assert np.max(np.abs(res[wl.EXP] - res[wl.SIG])) < 0.15
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
+def test_layer_steps_continue_a_layer_forward(variant, dtype):
+    """A prompt through tfla_mlstm_layer_fwd, then step by step through tfla_mlstm_layer_step: every y equals the layer
+    oracle's on the whole sequence."""
+    import paper_2503_14376_amd as tfla
+    from tests import gpu_util as gu
+    T0, NS = 128, 12
+    w = wl.small(variant, dtype, B=2, NH=3, T=T0 + NS, dqk=64, dhv=128, chunk=64, seed=63, init_state=False)
+    d = wl.make_layer_inputs(w, None, 2.0)
+    dev = _dev(w, d)
+    kw = dict(variant=variant, eps=1e-6, gate_softcap=15.0, norm_kind=lo.LAYER, norm_eps=1e-6)
+    cut = lambda key, lo_, hi: dev[key][:, :, lo_:hi].contiguous()
+    f = tfla.mlstm_layer_fwd(cut("q", 0, T0), cut("k", 0, T0), cut("v", 0, T0), cut("i_pre", 0, T0), cut("f_pre", 0, T0),
+                             cut("o_pre", 0, T0), dev["gamma"], dev["beta"], chunk=64, **kw)
+    C, n, m = f["Cn"], f["nn"], f["mn"]
+    ys = [f["Y"]]
+    for t in range(T0, T0 + NS):
+        at = lambda key: dev[key][:, :, t].contiguous()
+        s = tfla.mlstm_layer_step(at("q"), at("k"), at("v"), at("i_pre"), at("f_pre"), C, n if variant == wl.EXP else None,
+                                  m if variant == wl.EXP else None, at("o_pre"), dev["gamma"], dev["beta"], **kw)
+        C, n, m = s["C"], s["n"], s["m"]
+        ys.append(s["y"].unsqueeze(2))
+    torch.cuda.synchronize()
+    y = torch.cat(ys, dim=2)
+    ref = lo.layer_fwd(d["q"], d["k"], d["v"], d["i_pre"], d["f_pre"], d["o_pre"], d["gamma"], d["beta"], variant=variant,
+                       eps=1e-6, gate_softcap=15.0, kind=lo.LAYER, norm_eps=1e-6)
+    assert gu.rel_err(y, ref["y"]) <= gu.TOL[dtype]

@@ -231,3 +231,19 @@ def test_layer_argument_validation_happens_before_any_launch(tfla):
     assert gain(dtype=3) == -4
     assert gain(norm=2) == -4
     assert gain(neps=-1.0) == -2
+
+
+def test_layer_step_argument_validation(tfla):
+    lib = tfla.load_library()
+    P = lambda x: ctypes.c_void_p(x * 4096) if x else None
+    cf = ctypes.c_float
+
+    def call(y=1, h=1, norm=0, cap=0.0, dqk=256, n_out=1):
+        return lib.tfla_mlstm_layer_step(P(1), P(1), P(1), P(1), P(1), None, None, None, P(1), None, None, 2, 8, dqk, 512,
+                                         0, 1, cf(1e-6), cf(cap), norm, cf(1e-6), P(y), P(h), P(1), P(n_out), P(1), None)
+    assert call(y=0) == -1
+    assert call(h=0) == -1
+    assert call(n_out=0) == -1
+    assert call(norm=3) == -4
+    assert call(cap=-2.0) == -2
+    assert call(dqk=100) == -2
