@@ -4,7 +4,6 @@ import numpy as np
 import torch
 
 import workloads as wl
-from oracle import mlstm_oracle as orc
 
 TOL = {wl.BF16: 2e-2, wl.F32: 1e-4}   # max |gpu - ref| / max |ref| per output tensor
 
