@@ -68,3 +68,57 @@ def test_graph_replay_matches_eager(variant):
         graph.replay()
         check(ref)
         eager(dev2 if rep % 2 == 0 else dev)     # eager work of the same library between the replays
+
+
+def test_graph_replay_layer_with_ragged_length():
+    """The layer entry points with a sequence length that does not fill its last chunk (padding copies, gate soft-cap,
+    norm, parameter-gradient reduction): captured once, replayed with changing inputs, bit-equal to eager."""
+    import paper_2503_14376_amd as tfla
+    from tests.test_gpu_layer import _dev
+    B, NH, T, dqk, dhv, chunk, variant = 2, 2, 600, 64, 128, 256, wl.EXP
+    mk = lambda seed: wl.small(variant, wl.BF16, B=B, NH=NH, T=T, dqk=dqk, dhv=dhv, chunk=chunk, seed=seed, init_state=False)
+    devs = [_dev(mk(s), wl.make_layer_inputs(mk(s), None, 2.0)) for s in (91, 92)]
+    ws_f = torch.empty(tfla.layer_workspace_bytes(0, B, NH, T, dqk, dhv, chunk, variant, wl.BF16), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(tfla.layer_workspace_bytes(1, B, NH, T, dqk, dhv, chunk, variant, wl.BF16), dtype=torch.uint8, device="cuda")
+    kw = dict(chunk=chunk, variant=variant, eps=1e-6, gate_softcap=15.0, norm_kind=tfla.NORM_LAYER, norm_eps=1e-6)
+
+    def step(d, fo, bo, wf, wb):
+        tfla.mlstm_layer_fwd(d["q"], d["k"], d["v"], d["i_pre"], d["f_pre"], d["o_pre"], d["gamma"], d["beta"],
+                             workspace=wf, out=fo, **kw)
+        tfla.mlstm_layer_bwd(d["q"], d["k"], d["v"], d["i_pre"], d["f_pre"], fo["H"], d["dH"], d["o_pre"], d["gamma"],
+                             d["beta"], fo["n_out"], fo["m_out"], workspace=wb, out=bo, fwd_workspace=wf, **kw)
+
+    keys_f = ("Y", "H", "Cn", "n_out", "m_out")
+    keys_b = ("dq", "dk", "dv", "d_i_pre", "d_f_pre", "do_pre", "dgamma", "dbeta", "dC0")
+    snapshot = lambda fo, bo: [fo[k_].clone() for k_ in keys_f] + [bo[k_].clone() for k_ in keys_b]
+
+    def eager(d):
+        fo, bo = {}, {}
+        step(d, fo, bo, torch.empty_like(ws_f), torch.empty_like(ws_b))
+        torch.cuda.synchronize()
+        return snapshot(fo, bo)
+
+    refs = [eager(d) for d in devs]
+    g_in = {k_: v_.clone() for k_, v_ in devs[0].items()}
+    fo, bo = {}, {}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(g_in, fo, bo, ws_f, ws_b)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(g_in, fo, bo, ws_f, ws_b)
+    for rep in range(4):
+        for k_ in g_in:
+            g_in[k_].copy_(devs[rep % 2][k_])
+        for k_ in keys_f:
+            fo[k_].zero_()
+        for k_ in keys_b:
+            bo[k_].zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(snapshot(fo, bo), refs[rep % 2]):
+            assert torch.equal(got, want)
+        eager(devs[(rep + 1) % 2])
