@@ -77,14 +77,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     const int kc = __builtin_amdgcn_readfirstlane((int)(wg % a.Nc));
     const int bh = __builtin_amdgcn_readfirstlane((int)(wg / a.Nc));
     const long tbase = (long)bh * a.T + (long)kc * a.L;
-    // Which 32 rows of the workgroup a wavefront takes.  Under the causal mask the later rows of a row
-    // block meet more column tiles, and wavefront w of every workgroup runs on SIMD w: with two
-    // workgroups per CU every other workgroup reverses the order, so that a SIMD hosts a light and a
-    // heavy wavefront rather than two of a kind.
-    const unsigned hwid = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    const bool flip = OCC >= 2 && ((hwid >> 8) & 1u) != 0;
-    const int wrb = __builtin_amdgcn_readfirstlane(flip ? NW - 1 - wave : wave);
-    const int r0 = rb * BR, wr0 = r0 + wrb * 32;
+    const int r0 = rb * BR, wr0 = r0 + wave * 32;
     const int d2 = a.d2;
 
     const bf16_t* X = reinterpret_cast<const bf16_t*>(a.X);
@@ -195,7 +188,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             if (i + NS - 1 < NI) issue(i + NS - 1);
             const char* sb = smem + (i % NS) * STAGE;
 #pragma unroll
-            for (int ks = 0; ks < BXS / 16; ++ks) xf[i * (BXS / 16) + ks].v = rx.load(sb, ks, wrb);
+            for (int ks = 0; ks < BXS / 16; ++ks) xf[i * (BXS / 16) + ks].v = rx.load(sb, ks, wave);
         }
     }
 
@@ -297,7 +290,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     uint32_t eoff = 0;
     if constexpr (ELITE) {
         TFragReader<BR> re;  re.init(lane, 4);
-        eoff = re.block_offset(wrb);
+        eoff = re.block_offset(wave);
     }
     for (int ct = ct_lo; ct < ct_hi; ++ct) {
         const int i = NPRE + ct - ct_lo;
