@@ -458,7 +458,7 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
 
 extern "C" {
 
-int tfla_version(void) { return 1000; }
+int tfla_version(void) { return 1100; }
 
 int tfla_profile_enable(int max_launches) {
     if (g_prof.beg) {

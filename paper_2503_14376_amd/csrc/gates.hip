@@ -59,6 +59,9 @@ __device__ __forceinline__ float wave_excl_scan_max(float v, int lane) {
 // before any matrix product and no online rescaling is needed in the tiled kernel.
 static constexpr int GATE_WAVES = 4;
 
+// EC > 0: the lane's E <= EC steps keep their log gates in registers (one evaluation of the logarithms per
+// step instead of one per pass); EC = 0: any E, the log gates are evaluated again in every pass.
+template <int EC>
 __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a) {
     const int bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kc = blockIdx.x * GATE_WAVES + wave;
@@ -72,44 +75,60 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a
     const long t0 = (long)kc * a.L + (long)lane * E;
     // log gates of step t; the padding steps of a sequence that does not fill its last chunk keep the
     // state as it is (log forget gate 0) and add nothing (log input gate far below every other)
-    auto fbar = [&](long t) { return t < a.Tvalid ? log_sigmoid(soft_cap(a.f_pre[row + t], a.softcap)) : 0.0f; };
-    auto ibar = [&](long t) {
+    auto fbar_at = [&](long t) { return t < a.Tvalid ? log_sigmoid(soft_cap(a.f_pre[row + t], a.softcap)) : 0.0f; };
+    auto ibar_at = [&](long t) {
         if (t >= a.Tvalid) return -1.0e30f;
         const float ip = soft_cap(a.i_pre[row + t], a.softcap);
         return is_exp ? ip : log_sigmoid(ip);
     };
+    constexpr int NC = EC > 0 ? EC : 1;
+    float fbv[NC], ibv[NC];
+    if constexpr (EC > 0) {
+#pragma unroll
+        for (int e = 0; e < EC; ++e) {
+            fbv[e] = 0.0f; ibv[e] = 0.0f;
+            if (e < E) { fbv[e] = fbar_at(t0 + e); ibv[e] = ibar_at(t0 + e); }
+        }
+    }
+    auto fbar = [&](int e) { if constexpr (EC > 0) return fbv[e]; else return fbar_at(t0 + e); };
+    auto ibar = [&](int e) { if constexpr (EC > 0) return ibv[e]; else return ibar_at(t0 + e); };
+    const int EB = EC > 0 ? EC : E;                 // loop bound (compile-time when the gates are cached)
     float fsum = 0.0f;
-    for (int e = 0; e < E; ++e) fsum += fbar(t0 + e);
+#pragma unroll
+    for (int e = 0; e < EB; ++e)
+        if (e < E) fsum += fbar(e);
     const float off = wave_excl_scan_add(fsum, lane);
     const float roff = wave_excl_rscan_add(fsum, lane);
     // forward pass: b, u = i-bar - b, running max of u
     float b = off, cmx = -INFINITY;
-    for (int e = 0; e < E; ++e) {
-        const float fb = fbar(t0 + e);
-        const float ib = ibar(t0 + e);
-        b += fb;
-        cmx = fmaxf(cmx, ib - b);
-    }
+#pragma unroll
+    for (int e = 0; e < EB; ++e)
+        if (e < E) {
+            b += fbar(e);
+            cmx = fmaxf(cmx, ibar(e) - b);
+        }
     const float cmoff = wave_excl_scan_max(cmx, lane);
     b = off; cmx = cmoff;
-    for (int e = 0; e < E; ++e) {
-        const float fb = fbar(t0 + e);
-        const float ib = ibar(t0 + e);
-        b += fb;
-        const float u = ib - b;
-        cmx = fmaxf(cmx, u);
-        tb[t0 + e] = b;
-        tc[t0 + e] = cmx;
-        a.ucol[row + t0 + e] = u * LOG2E;
-    }
+#pragma unroll
+    for (int e = 0; e < EB; ++e)
+        if (e < E) {
+            b += fbar(e);
+            const float u = ibar(e) - b;
+            cmx = fmaxf(cmx, u);
+            tb[t0 + e] = b;
+            tc[t0 + e] = cmx;
+            a.ucol[row + t0 + e] = u * LOG2E;
+        }
     // reverse pass: a_j = sum_{s>j} f-bar_s + i-bar_j
     float run = roff, amax = -INFINITY;
-    for (int e = E - 1; e >= 0; --e) {
-        const float av = run + ibar(t0 + e);
-        ta[t0 + e] = av;
-        amax = fmaxf(amax, av);
-        run += fbar(t0 + e);
-    }
+#pragma unroll
+    for (int e = EB - 1; e >= 0; --e)
+        if (e < E) {
+            const float av = run + ibar(e);
+            ta[t0 + e] = av;
+            amax = fmaxf(amax, av);
+            run += fbar(e);
+        }
     amax = wave_max(amax);
     const float gsum = wave_sum(fsum);
     if (lane == 0) {
@@ -187,7 +206,8 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_step_kernel(GateArgs a)
 
 hipError_t launch_gates(const GateArgs& a, int BH, hipStream_t s) {
     const dim3 grid((a.Nc + GATE_WAVES - 1) / GATE_WAVES, BH);
-    hipLaunchKernelGGL(gates_chunk_kernel, grid, dim3(GATE_WAVES * 64), 0, s, a);
+    if (a.L / 64 <= 8) hipLaunchKernelGGL(gates_chunk_kernel<8>, grid, dim3(GATE_WAVES * 64), 0, s, a);
+    else hipLaunchKernelGGL(gates_chunk_kernel<0>, grid, dim3(GATE_WAVES * 64), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(gates_step_kernel, grid, dim3(GATE_WAVES * 64), sizeof(float) * (size_t)(a.Nc + 1), s, a);
