@@ -213,19 +213,21 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         const char* sb = smem + ((NXS + i) % NS) * STAGE;
         constexpr int KSS = BCS / 16, NF = KSS * NB;
         if constexpr (OCC == 1) {
-            frag b[KSS][NB];
             // one wavefront per SIMD: nothing else hides the time the request spends in the memory
-            // pipeline's queue, so it is spread between the matrix instructions; all fragments of the
-            // slice are read first
+            // pipeline's queue, so it is spread between the matrix instructions; the fragments of k step
+            // ks + 1 are read while the matrix instructions of k step ks run
+            frag b[2][NB];
 #pragma unroll
-            for (int ks = 0; ks < KSS; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    b[ks][nb].v = STT ? rzn.load(sb, nb, 16 * ks, 16 * ks + 4) : rs_.load(sb, ks, nb);
+            for (int nb = 0; nb < NB; ++nb) b[0][nb].v = STT ? rzn.load(sb, nb, 0, 4) : rs_.load(sb, 0, nb);
 #pragma unroll
             for (int ks = 0; ks < KSS; ++ks) {
+                if (ks + 1 < KSS) {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks][nb], xf[i * KSS + ks], acc[nb]);
+                    for (int nb = 0; nb < NB; ++nb)
+                        b[(ks + 1) & 1][nb].v = STT ? rzn.load(sb, nb, 16 * (ks + 1), 16 * (ks + 1) + 4) : rs_.load(sb, ks + 1, nb);
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks & 1][nb], xf[i * KSS + ks], acc[nb]);
                 if (req) issue_part(NXS + i + NS - 1, ks, KSS);
             }
         } else {
