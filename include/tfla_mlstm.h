@@ -26,13 +26,16 @@
  *  - variant TFLA_SIG has no normaliser and no max state: n0, m0 and eps are ignored and
  *    nn, mn, n_out, m_out are filled with zeros when non-NULL.
  *  - eps is added to the denominator max{|n^T q~|, exp(-m)}; eps = 0 is the paper's formula.
- *  - Restrictions: chunk % 64 == 0, 64 <= chunk <= 2048, ceil(T / chunk) <= 4096, dqk and dhv in {64, 128, 256, 512} (at most 256 for TFLA_F32),
+ *  - Restrictions: chunk % 64 == 0, 64 <= chunk <= 2048, ceil(T / chunk) <= 4096, dqk and dhv
+ *    multiples of 8, at most 512 (at most 256 for TFLA_F32),
  *    B * NH <= 65535.
- *  - T need not be a multiple of chunk (N_c = ceil(T / chunk), Sec. 2.2).  The kernels work on whole
- *    chunks: for such a T the library copies the inputs into zero-padded buffers inside the workspace
+ *  - T need not be a multiple of chunk (N_c = ceil(T / chunk), Sec. 2.2), and the head dimensions need
+ *    not be among the kernels' own widths 64, 128, 256, 512.  The kernels work on whole chunks and on
+ *    those widths: otherwise the library copies the inputs into zero-padded buffers inside the workspace
  *    (which is correspondingly larger, see tfla_mlstm_workspace_bytes), gives the padding steps a forget
- *    gate of one and an input gate of zero, and copies the first T steps of the results back, so the
- *    result is that of the T-step sequence; tensor pointers must then be 16-byte aligned (TFLA_ERR_SHAPE).
+ *    gate of one and an input gate of zero, scales q by 1/sqrt of the true dqk, and copies the true part
+ *    of the results back, so the result is that of the problem as given; tensor and state pointers must
+ *    then be 16-byte aligned (TFLA_ERR_SHAPE).
  *  - Return value: TFLA_OK (0) on success; a negative TFLA_ERR_* code for an invalid
  *    argument (checked before anything is launched, nothing is written); a positive value is
  *    the hipError_t of a failed launch.  No entry point throws or aborts.

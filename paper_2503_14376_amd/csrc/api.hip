@@ -18,13 +18,20 @@ struct Dims {
     size_t esz;
 };
 
-int check_dims(int direction, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype) {
+// the head dimension the kernels run a caller's head dimension at (zero-padded columns in between)
+inline int kernel_dim(int d) { return d <= 64 ? 64 : (d <= 128 ? 128 : (d <= 256 ? 256 : 512)); }
+
+// core = true: the kernels' own widths only (what the kernel sequences are called with)
+int check_dims(int direction, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype, bool core = false) {
     if (direction != TFLA_FWD && direction != TFLA_BWD) return TFLA_ERR_ENUM;
     if (variant != TFLA_EXP && variant != TFLA_SIG) return TFLA_ERR_ENUM;
     if (dtype != TFLA_F32 && dtype != TFLA_BF16) return TFLA_ERR_ENUM;
     if (B <= 0 || NH <= 0 || T <= 0 || dqk <= 0 || dhv <= 0) return TFLA_ERR_SHAPE;
     const int dmax = dtype == TFLA_BF16 ? 512 : 256;
-    auto ok_d = [&](int d) { return (d == 64 || d == 128 || d == 256 || d == 512) && d <= dmax; };
+    auto ok_d = [&](int d) {
+        if (d > dmax || d % 8 != 0) return false;
+        return !core || d == 64 || d == 128 || d == 256 || d == 512;
+    };
     if (!ok_d(dqk) || !ok_d(dhv)) return TFLA_ERR_SHAPE;
     if ((long)B * NH > 65535) return TFLA_ERR_SHAPE;
     if (chunk < 64 || chunk > 2048 || chunk % 64 != 0) return TFLA_ERR_CHUNK;
@@ -97,8 +104,8 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.csum = c.take<float>(2 * d.BH * d.Nc);
     w.bsum = c.take<double>(d.BH * ((d.T + 1023) / 1024));
     w.wrowB = c.take<float>(d.BHT); w.sQ = c.take<float>(d.BHT);
-    w.nbQ = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DQ);
-    w.nbK = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DK);
+    w.nbQ = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DQ, d.L);
+    w.nbK = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DK, d.L);
     w.partQ = c.take<float>((size_t)w.nbQ * d.BHT); w.partK = c.take<float>((size_t)w.nbK * d.BHT);
     w.cdot = c.take<float>(d.BH);
     w.Cfinal = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
@@ -169,12 +176,12 @@ void prof_collect() {
 
 int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float* m0, float* wrow, float* ucol,
               float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, float* csum, float softcap,
-              int Tvalid, hipStream_t s) {
+              int Tvalid, int dqk_true, hipStream_t s) {
     GateArgs g;
     g.softcap = softcap; g.Tvalid = Tvalid;
     g.i_pre = i_pre; g.f_pre = f_pre; g.m0 = d.variant == TFLA_EXP ? m0 : nullptr;
     g.T = d.T; g.L = d.L; g.Nc = d.Nc; g.variant = d.variant;
-    g.qscale = 1.0f / sqrtf((float)d.dqk);
+    g.qscale = 1.0f / sqrtf((float)dqk_true);   // of the caller's head dimension, not of the padded one
     g.wrow = wrow; g.ucol = ucol; g.sH = sH; g.aK = aK; g.gbar = gbar; g.mout = mout; g.mfinal = mfinal; g.tmp = tmp; g.csum = csum;
     TFLA_LAUNCH(K_GATES, launch_gates(g, (int)d.BH, s));
     return TFLA_OK;
@@ -182,10 +189,10 @@ int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float
 
 // Forward pass over whole chunks: T is a multiple of chunk, steps >= Tvalid are padding.
 int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
-             const float* n0, const float* m0, int B, int NH, int T, int Tvalid, int dqk, int dhv, int chunk, int variant,
-             int dtype, float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
+             const float* n0, const float* m0, int B, int NH, int T, int Tvalid, int dqk_true, int dqk, int dhv, int chunk,
+             int variant, int dtype, float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
              void* workspace, size_t workspace_bytes, void* stream) {
-    const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype, true);
     if (rc != TFLA_OK) return rc;
     if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
     if (variant == TFLA_EXP) {
@@ -201,7 +208,7 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
     // 1. gates, max states
     float* mout = (is_exp && m_out) ? m_out : w.mout;
-    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, softcap, Tvalid, s);
+    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, softcap, Tvalid, dqk_true, s);
     if (st != TFLA_OK) return st;
 
     // 2. recurrent kernel: C_{k-1} (transposed, element type of q/k/v) and n_{k-1} for every chunk
@@ -233,10 +240,11 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
 int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
              const float* n0, const float* m0, const float* n_out, const float* m_out, const void* dH, const float* dCn,
-             int B, int NH, int T, int Tvalid, int dqk, int dhv, int chunk, int variant, int dtype, float eps, float softcap, void* dq,
+             int B, int NH, int T, int Tvalid, int dqk_true, int dqk, int dhv, int chunk, int variant, int dtype, float eps,
+             float softcap, void* dq,
              void* dk, void* dv, float* d_i_pre, float* d_f_pre, float* dC0, const void* fwd_workspace,
              size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, void* stream) {
-    const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype, true);
     if (rc != TFLA_OK) return rc;
     if (!q || !k || !v || !i_pre || !f_pre || !dH || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
     const bool is_exp = variant == TFLA_EXP;
@@ -272,7 +280,7 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
     // 1. gates as in the forward pass, then fold 1/h_denom into the backward weights
     if (!reuse) {
-        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, softcap, Tvalid, s);
+        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, softcap, Tvalid, dqk_true, s);
         if (st != TFLA_OK) return st;
     }
     GateBwdPrepArgs p;
@@ -329,21 +337,32 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 }
 
 
-// ---- sequence lengths that do not fill the last chunk -------------------------------------------
-// The cores work on whole chunks.  For a ragged T the entry points copy the inputs into buffers of
-// Nc * chunk steps behind the core's own workspace (zero rows past T), run the core there with
-// Tvalid = T, and copy the first T steps of the per-step outputs back.
-struct PadFwd { void *q, *k, *v, *H; float *ip, *fp, *nout, *mout; size_t bytes; };
+// ---- sequence lengths that do not fill the last chunk, head dimensions between the kernels' own -------
+// The cores work on whole chunks and on head dimensions 64, 128, 256, 512.  For any other T or head
+// dimension the entry points copy the inputs into zero-padded buffers behind the core's own workspace,
+// run the core there (Tvalid = T, the 1/sqrt(dqk) of the true dqk), and copy the true part of the outputs
+// back.  `d` below always describes the padded problem.
+struct PadFwd {
+    void *q, *k, *v, *H;
+    float *ip, *fp, *nout, *mout, *C0, *n0, *Cn, *nn;
+    size_t bytes;
+};
 PadFwd carve_pad_fwd(const Dims& d, void* base) {
     Carver c(base);
     PadFwd p;
     p.q = c.take_bytes((size_t)d.BHT * d.dqk * d.esz); p.k = c.take_bytes((size_t)d.BHT * d.dqk * d.esz);
     p.v = c.take_bytes((size_t)d.BHT * d.dhv * d.esz); p.H = c.take_bytes((size_t)d.BHT * d.dhv * d.esz);
     p.ip = c.take<float>(d.BHT); p.fp = c.take<float>(d.BHT); p.nout = c.take<float>(d.BHT); p.mout = c.take<float>(d.BHT);
+    p.C0 = c.take<float>((size_t)d.BH * d.dqk * d.dhv); p.n0 = c.take<float>((size_t)d.BH * d.dqk);
+    p.Cn = c.take<float>((size_t)d.BH * d.dqk * d.dhv); p.nn = c.take<float>((size_t)d.BH * d.dqk);
     p.bytes = c.off;
     return p;
 }
-struct PadBwd { void *q, *k, *v, *dH, *dq, *dk, *dv; float *ip, *fp, *nout, *mout, *di, *df; size_t bytes; };
+struct PadBwd {
+    void *q, *k, *v, *dH, *dq, *dk, *dv;
+    float *ip, *fp, *nout, *mout, *di, *df, *C0, *n0, *dCn, *dC0;
+    size_t bytes;
+};
 PadBwd carve_pad_bwd(const Dims& d, void* base) {
     Carver c(base);
     PadBwd p;
@@ -352,16 +371,22 @@ PadBwd carve_pad_bwd(const Dims& d, void* base) {
     p.dq = c.take_bytes(sq); p.dk = c.take_bytes(sq); p.dv = c.take_bytes(sv);
     p.ip = c.take<float>(d.BHT); p.fp = c.take<float>(d.BHT); p.nout = c.take<float>(d.BHT); p.mout = c.take<float>(d.BHT);
     p.di = c.take<float>(d.BHT); p.df = c.take<float>(d.BHT);
+    const size_t ss = (size_t)d.BH * d.dqk * d.dhv;
+    p.C0 = c.take<float>(ss); p.n0 = c.take<float>((size_t)d.BH * d.dqk); p.dCn = c.take<float>(ss); p.dC0 = c.take<float>(ss);
     p.bytes = c.off;
     return p;
 }
-size_t fwd_total_bytes(const Dims& d, int T) {
-    return carve_fwd(d, nullptr).bytes + (T == d.T ? 0 : carve_pad_fwd(d, nullptr).bytes);
+// dp: the padded problem; padded = whether the caller's problem differs from it
+size_t fwd_total_bytes(const Dims& dp, bool padded) {
+    return carve_fwd(dp, nullptr).bytes + (padded ? carve_pad_fwd(dp, nullptr).bytes : 0);
 }
-size_t bwd_total_bytes(const Dims& d, int T) {
-    return carve_bwd(d, nullptr).bytes + (T == d.T ? 0 : carve_pad_bwd(d, nullptr).bytes);
+size_t bwd_total_bytes(const Dims& dp, bool padded) {
+    return carve_bwd(dp, nullptr).bytes + (padded ? carve_pad_bwd(dp, nullptr).bytes : 0);
 }
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+inline bool needs_pad(int T, int dqk, int dhv, int chunk) {
+    return T % chunk != 0 || dqk != kernel_dim(dqk) || dhv != kernel_dim(dhv);
+}
 
 int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
              const float* n0, const float* m0, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype,
@@ -369,34 +394,48 @@ int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
              void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
     if (rc != TFLA_OK) return rc;
-    if (T % chunk == 0)
-        return fwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, T, dqk, dhv, chunk, variant, dtype, eps, softcap, H, Cn,
-                        nn, mn, n_out, m_out, workspace, workspace_bytes, stream);
+    if (!needs_pad(T, dqk, dhv, chunk))
+        return fwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, T, dqk, dqk, dhv, chunk, variant, dtype, eps, softcap, H,
+                        Cn, nn, mn, n_out, m_out, workspace, workspace_bytes, stream);
     if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
-    if (variant == TFLA_EXP) {
+    const bool is_exp = variant == TFLA_EXP;
+    if (is_exp) {
         const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
         if (given != 0 && given != 3) return TFLA_ERR_STATE;
     }
-    if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(H)) return TFLA_ERR_SHAPE;
-    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(H) || misaligned16(C0) || misaligned16(Cn))
+        return TFLA_ERR_SHAPE;
+    const int dq_p = kernel_dim(dqk), dv_p = kernel_dim(dhv);
+    const Dims d = make_dims(B, NH, T, dq_p, dv_p, chunk, variant, dtype);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
     const size_t core_bytes = carve_fwd(d, nullptr).bytes;
     const PadFwd p = carve_pad_fwd(d, reinterpret_cast<char*>(workspace) + core_bytes);
     if (workspace_bytes < core_bytes + p.bytes) return TFLA_ERR_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const int Tp = d.T;
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, dqk * (int)d.esz, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, dqk * (int)d.esz, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, dhv * (int)d.esz, s));
+    const int Tp = d.T, es = (int)d.esz;
+    const bool dpad = dq_p != dqk || dv_p != dhv;       // states need padding too
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, dqk * es, dq_p * es, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, dqk * es, dq_p * es, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, dhv * es, dv_p * es, s));
     TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
     TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
-    const int st = fwd_core(p.q, p.k, p.v, p.ip, p.fp, C0, n0, m0, B, NH, Tp, T, dqk, dhv, chunk, variant, dtype, eps,
-                            softcap, p.H, Cn, nn, mn, n_out ? p.nout : nullptr, m_out ? p.mout : nullptr, workspace,
+    const float* C0c = C0; const float* n0c = n0;
+    if (dpad && C0) {
+        TFLA_LAUNCH(K_PAD, launch_pad_rows(C0, p.C0, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
+        C0c = p.C0;
+        if (is_exp) { TFLA_LAUNCH(K_PAD, launch_pad_scalar(n0, p.n0, d.BH, dqk, dq_p, 0.0f, s)); n0c = p.n0; }
+    }
+    float* Cnc = (dpad && Cn) ? p.Cn : Cn;
+    float* nnc = (dpad && nn) ? p.nn : nn;
+    const int st = fwd_core(p.q, p.k, p.v, p.ip, p.fp, C0c, n0c, m0, B, NH, Tp, T, dqk, dq_p, dv_p, chunk, variant, dtype, eps,
+                            softcap, p.H, Cnc, nnc, mn, n_out ? p.nout : nullptr, m_out ? p.mout : nullptr, workspace,
                             core_bytes, stream);
     if (st != TFLA_OK) return st;
-    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.H, H, d.BH, T, Tp, dhv * (int)d.esz, s));
+    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.H, H, d.BH, T, Tp, dhv * es, dv_p * es, s));
     if (n_out) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.nout, n_out, d.BH, T, Tp, s));
     if (m_out) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.mout, m_out, d.BH, T, Tp, s));
+    if (dpad && Cn) TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.Cn, Cn, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
+    if (dpad && nn) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.nn, nn, d.BH, dqk, dq_p, s));
     return TFLA_OK;
 }
 
@@ -407,8 +446,8 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
              size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
     if (rc != TFLA_OK) return rc;
-    if (T % chunk == 0)
-        return bwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, n_out, m_out, dH, dCn, B, NH, T, T, dqk, dhv, chunk, variant,
+    if (!needs_pad(T, dqk, dhv, chunk))
+        return bwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, n_out, m_out, dH, dCn, B, NH, T, T, dqk, dqk, dhv, chunk, variant,
                         dtype, eps, softcap, dq, dk, dv, d_i_pre, d_f_pre, dC0, fwd_workspace, fwd_workspace_bytes,
                         workspace, workspace_bytes, stream);
     if (!q || !k || !v || !i_pre || !f_pre || !dH || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
@@ -419,9 +458,10 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
         if (given != 0 && given != 3) return TFLA_ERR_STATE;
     }
     if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(dH) || misaligned16(dq) || misaligned16(dk) ||
-        misaligned16(dv))
+        misaligned16(dv) || misaligned16(C0) || misaligned16(dCn) || misaligned16(dC0))
         return TFLA_ERR_SHAPE;
-    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    const int dq_p = kernel_dim(dqk), dv_p = kernel_dim(dhv);
+    const Dims d = make_dims(B, NH, T, dq_p, dv_p, chunk, variant, dtype);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
     if (fwd_workspace && ((reinterpret_cast<uintptr_t>(fwd_workspace) & 255) != 0 ||
                           fwd_workspace_bytes < carve_fwd(d, nullptr).bytes))
@@ -430,11 +470,12 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
     const PadBwd p = carve_pad_bwd(d, reinterpret_cast<char*>(workspace) + core_bytes);
     if (workspace_bytes < core_bytes + p.bytes) return TFLA_ERR_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const int Tp = d.T, eq = dqk * (int)d.esz, ev = dhv * (int)d.esz;
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, eq, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, eq, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, ev, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(dH, p.dH, d.BH, T, Tp, ev, s));
+    const int Tp = d.T, es = (int)d.esz, eq = dqk * es, ev = dhv * es, eqp = dq_p * es, evp = dv_p * es;
+    const bool dpad = dq_p != dqk || dv_p != dhv;
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, eq, eqp, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, eq, eqp, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, ev, evp, s));
+    TFLA_LAUNCH(K_PAD, launch_pad_rows(dH, p.dH, d.BH, T, Tp, ev, evp, s));
     TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
     TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
     if (is_exp) {
@@ -442,15 +483,27 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
         TFLA_LAUNCH(K_PAD, launch_pad_scalar(n_out, p.nout, d.BH, T, Tp, 1.0f, s));
         TFLA_LAUNCH(K_PAD, launch_pad_scalar(m_out, p.mout, d.BH, T, Tp, 0.0f, s));
     }
-    const int st = bwd_core(p.q, p.k, p.v, p.ip, p.fp, C0, n0, m0, is_exp ? p.nout : nullptr, is_exp ? p.mout : nullptr,
-                            p.dH, dCn, B, NH, Tp, T, dqk, dhv, chunk, variant, dtype, eps, softcap, p.dq, p.dk, p.dv, p.di,
-                            p.df, dC0, fwd_workspace, fwd_workspace_bytes, workspace, core_bytes, stream);
+    const float* C0c = C0; const float* n0c = n0; const float* dCnc = dCn;
+    if (dpad && C0) {
+        TFLA_LAUNCH(K_PAD, launch_pad_rows(C0, p.C0, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
+        C0c = p.C0;
+        if (is_exp) { TFLA_LAUNCH(K_PAD, launch_pad_scalar(n0, p.n0, d.BH, dqk, dq_p, 0.0f, s)); n0c = p.n0; }
+    }
+    if (dpad && dCn) {
+        TFLA_LAUNCH(K_PAD, launch_pad_rows(dCn, p.dCn, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
+        dCnc = p.dCn;
+    }
+    float* dC0c = (dpad && dC0) ? p.dC0 : dC0;
+    const int st = bwd_core(p.q, p.k, p.v, p.ip, p.fp, C0c, n0c, m0, is_exp ? p.nout : nullptr, is_exp ? p.mout : nullptr,
+                            p.dH, dCnc, B, NH, Tp, T, dqk, dq_p, dv_p, chunk, variant, dtype, eps, softcap, p.dq, p.dk, p.dv,
+                            p.di, p.df, dC0c, fwd_workspace, fwd_workspace_bytes, workspace, core_bytes, stream);
     if (st != TFLA_OK) return st;
-    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dq, dq, d.BH, T, Tp, eq, s));
-    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dk, dk, d.BH, T, Tp, eq, s));
-    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dv, dv, d.BH, T, Tp, ev, s));
+    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dq, dq, d.BH, T, Tp, eq, eqp, s));
+    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dk, dk, d.BH, T, Tp, eq, eqp, s));
+    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dv, dv, d.BH, T, Tp, ev, evp, s));
     TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.di, d_i_pre, d.BH, T, Tp, s));
     TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.df, d_f_pre, d.BH, T, Tp, s));
+    if (dpad && dC0) TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dC0, dC0, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
     return TFLA_OK;
 }
 
@@ -517,8 +570,9 @@ int tfla_mlstm_check(int direction, int B, int NH, int T, int dqk, int dhv, int 
 size_t tfla_mlstm_workspace_bytes(int direction, int B, int NH, int T, int dqk, int dhv, int chunk, int variant,
                                   int dtype) {
     if (check_dims(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) != TFLA_OK) return 0;
-    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
-    return direction == TFLA_FWD ? fwd_total_bytes(d, T) : bwd_total_bytes(d, T);
+    const Dims d = make_dims(B, NH, T, kernel_dim(dqk), kernel_dim(dhv), chunk, variant, dtype);
+    const bool padded = needs_pad(T, dqk, dhv, chunk);
+    return direction == TFLA_FWD ? fwd_total_bytes(d, padded) : bwd_total_bytes(d, padded);
 }
 
 int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
@@ -640,12 +694,13 @@ int tfla_mlstm_layer_bwd(const void* q, const void* k, const void* v, const floa
         const int given = (C0 != nullptr) + (n0 != nullptr) + (m0 != nullptr);
         if (given != 0 && given != 3) return TFLA_ERR_STATE;
     }
-    const Dims d = make_dims(B, NH, T, dqk, dhv, chunk, variant, dtype);
+    // d: the problem the cell's kernels run (whole chunks, their own head dimensions)
+    const Dims d = make_dims(B, NH, T, kernel_dim(dqk), kernel_dim(dhv), chunk, variant, dtype);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return TFLA_ERR_WORKSPACE;
     if (fwd_workspace && ((reinterpret_cast<uintptr_t>(fwd_workspace) & 255) != 0 ||
                           fwd_workspace_bytes < carve_fwd(d, nullptr).bytes))
         return TFLA_ERR_WORKSPACE;
-    const size_t base = bwd_total_bytes(d, T);
+    const size_t base = bwd_total_bytes(d, needs_pad(T, dqk, dhv, chunk));
     const int nblk = norm_row_blocks(T);
     Carver c(reinterpret_cast<char*>(workspace) + base);
     void* dHt = c.take_bytes((size_t)d.BH * T * dhv * d.esz);

@@ -1,7 +1,10 @@
-// Sequence lengths that are not a multiple of the chunk size (App. B.2 defines N_c = ceil(T / L)):
-// the kernels work on whole chunks, so the library copies the inputs into buffers of N_c L steps
-// per (batch, head) inside the caller's workspace, zero-filling the steps past T, runs the
-// kernels there, and copies the first T steps of the results back.  A zero k, v (and upstream
+// Sequence lengths that are not a multiple of the chunk size (App. B.2 defines N_c = ceil(T / L))
+// and head dimensions between the kernels' own (64, 128, 256, 512):
+// the kernels work on whole chunks and on those widths, so the library copies the inputs into
+// buffers of N_c L steps per (batch, head) and the next supported width inside the caller's
+// workspace, zero-filling the steps past T and the columns past the head dimension, runs the
+// kernels there, and copies the first T steps and the true columns of the results back.  Zero
+// columns of q and k add nothing to any q . k, zero columns of v give zero columns of the output.  A zero k, v (and upstream
 // gradient) row contributes nothing to any state, output or gradient, and the gate kernels give
 // the padded steps a forget gate of one and an input gate of zero, so the result is exactly
 // that of the shorter sequence.
@@ -12,21 +15,22 @@ namespace tfla {
 
 namespace {
 
-// rows of `rw` 16-byte words; (BH, T, rw) -> (BH, Tp, rw)
-__global__ void __launch_bounds__(256) pad_rows_kernel(const uint4* in, uint4* out, long total, int T, int Tp, int rw) {
+// rows of 16-byte words; (BH, T, rw) -> (BH, Tp, rwp), zero outside the source
+__global__ void __launch_bounds__(256) pad_rows_kernel(const uint4* in, uint4* out, long total, int T, int Tp, int rw, int rwp) {
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
-        const long bh = i / ((long)Tp * rw);
-        const long rem = i - bh * (long)Tp * rw;
-        const int t = (int)(rem / rw), w = (int)(rem - (long)t * rw);
-        out[i] = t < T ? in[((long)bh * T + t) * rw + w] : make_uint4(0u, 0u, 0u, 0u);
+        const long bh = i / ((long)Tp * rwp);
+        const long rem = i - bh * (long)Tp * rwp;
+        const int t = (int)(rem / rwp), w = (int)(rem - (long)t * rwp);
+        out[i] = (t < T && w < rw) ? in[((long)bh * T + t) * rw + w] : make_uint4(0u, 0u, 0u, 0u);
     }
 }
-// (BH, Tp, rw) -> (BH, T, rw)
-__global__ void __launch_bounds__(256) unpad_rows_kernel(const uint4* in, uint4* out, long total, int T, int Tp, int rw) {
+// (BH, Tp, rwp) -> (BH, T, rw)
+__global__ void __launch_bounds__(256) unpad_rows_kernel(const uint4* in, uint4* out, long total, int T, int Tp, int rw, int rwp) {
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
         const long bh = i / ((long)T * rw);
         const long rem = i - bh * (long)T * rw;
-        out[i] = in[bh * (long)Tp * rw + rem];
+        const int t = (int)(rem / rw), w = (int)(rem - (long)t * rw);
+        out[i] = in[(bh * (long)Tp + t) * rwp + w];
     }
 }
 __global__ void __launch_bounds__(256) pad_scalar_kernel(const float* in, float* out, long total, int T, int Tp, float fill) {
@@ -50,18 +54,18 @@ inline unsigned grid_for(long total) {
 
 }  // namespace
 
-hipError_t launch_pad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, hipStream_t s) {
-    const int rw = row_bytes / 16;
-    const long total = BH * (long)Tp * rw;
+hipError_t launch_pad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, int row_bytes_p, hipStream_t s) {
+    const int rw = row_bytes / 16, rwp = row_bytes_p / 16;
+    const long total = BH * (long)Tp * rwp;
     hipLaunchKernelGGL(pad_rows_kernel, dim3(grid_for(total)), dim3(256), 0, s, reinterpret_cast<const uint4*>(in),
-                       reinterpret_cast<uint4*>(out), total, T, Tp, rw);
+                       reinterpret_cast<uint4*>(out), total, T, Tp, rw, rwp);
     return hipGetLastError();
 }
-hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, hipStream_t s) {
-    const int rw = row_bytes / 16;
+hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, int row_bytes_p, hipStream_t s) {
+    const int rw = row_bytes / 16, rwp = row_bytes_p / 16;
     const long total = BH * (long)T * rw;
     hipLaunchKernelGGL(unpad_rows_kernel, dim3(grid_for(total)), dim3(256), 0, s, reinterpret_cast<const uint4*>(in),
-                       reinterpret_cast<uint4*>(out), total, T, Tp, rw);
+                       reinterpret_cast<uint4*>(out), total, T, Tp, rw, rwp);
     return hipGetLastError();
 }
 hipError_t launch_pad_scalar(const float* in, float* out, long BH, int T, int Tp, float fill, hipStream_t s) {

@@ -48,10 +48,10 @@ struct GateGradArgs {
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
 
 hipError_t launch_fill_zero(float* p, long n, hipStream_t s);
-// (BH, T, row) <-> (BH, Tp, row) copies for sequence lengths that are not a multiple of the chunk (pad.hip);
-// row_bytes a multiple of 16, pointers 16-byte aligned
-hipError_t launch_pad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, hipStream_t s);
-hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, hipStream_t s);
+// (BH, T, row) <-> (BH, Tp, row_p) copies for sequence lengths that are not a multiple of the chunk and head
+// dimensions between the supported ones (pad.hip); row bytes multiples of 16, pointers 16-byte aligned
+hipError_t launch_pad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, int row_bytes_p, hipStream_t s);
+hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, int row_bytes_p, hipStream_t s);
 hipError_t launch_pad_scalar(const float* in, float* out, long BH, int T, int Tp, float fill, hipStream_t s);
 hipError_t launch_unpad_scalar(const float* in, float* out, long BH, int T, int Tp, hipStream_t s);
 hipError_t launch_state_dot(const float* A, const float* Bm, float* out, long per, int BH, hipStream_t s);
@@ -151,8 +151,10 @@ template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int d
 // wavefront within 256 registers, so that two workgroups share a CU when d1 <= 256.  The bf16 dQ and
 // dK kernels take a 256-wide block when d1 = 512 (one workgroup per CU anyway): half as many
 // workgroups fetch the same X rows and column tiles, and dQ computes S once per 256 columns.
-inline int tile_bd2(int d1, int d2, int dtype, int mode) {
-    if (dtype == 1 && (mode == MODE_DK || mode == MODE_DQ) && d1 == 512 && d2 % 256 == 0) return 256;
+// (The 256-wide instantiations exist for the four-wavefront workgroups only, i.e. for chunk sizes that are
+// multiples of 128.)
+inline int tile_bd2(int d1, int d2, int dtype, int mode, int L) {
+    if (dtype == 1 && (mode == MODE_DK || mode == MODE_DQ) && d1 == 512 && d2 % 256 == 0 && L % 128 == 0) return 256;
     if (d2 % 128 == 0) return 128;
     return 64;
 }

@@ -263,10 +263,12 @@ static hipError_t launch_tile_d1(const TileArgs& a, int BH, int bd2, hipStream_t
             if (bd2 == 256) return launch_tile_t<DT, D1, 256, 4, MODE>(a, BH, s);
         }
         if (bd2 == 128) return launch_tile_t<DT, D1, 128, 4, MODE>(a, BH, s);
-        return launch_tile_t<DT, D1, 64, 4, MODE>(a, BH, s);
+        if (bd2 == 64) return launch_tile_t<DT, D1, 64, 4, MODE>(a, BH, s);
+        return hipErrorInvalidValue;    // the caller sized its buffers for a block width that is not built
     }
     if (bd2 == 128) return launch_tile_t<DT, D1, 128, 2, MODE>(a, BH, s);
-    return launch_tile_t<DT, D1, 64, 2, MODE>(a, BH, s);
+    if (bd2 == 64) return launch_tile_t<DT, D1, 64, 2, MODE>(a, BH, s);
+    return hipErrorInvalidValue;
 }
 
 template <typename DT, int MODE>
@@ -285,7 +287,7 @@ static hipError_t launch_tile_m(const TileArgs& a, int BH, int bd2, hipStream_t 
 
 template <int MODE>
 hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s) {
-    const int bd2 = tile_bd2(a.d1, a.d2, dtype, MODE);
+    const int bd2 = tile_bd2(a.d1, a.d2, dtype, MODE, a.L);
     return dtype == 1 ? launch_tile_m<bf16_t, MODE>(a, BH, bd2, s) : launch_tile_m<float, MODE>(a, BH, bd2, s);
 }
 

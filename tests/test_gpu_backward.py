@@ -59,3 +59,11 @@ def test_bwd_small(variant, dtype, shape):
 @pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
 def test_bwd_7b_head_shape_bf16(variant):
     run_case(wl.small(variant, wl.BF16, B=1, NH=1, T=1024, dqk=256, dhv=512, chunk=256, seed=41), with_dCn=True)
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("chunk", [64, 192])
+def test_bwd_wide_heads_with_chunks_that_are_not_multiples_of_128(variant, chunk):
+    # the 512-wide contraction of dQ / dK with the two-wavefront workgroups (their block width differs from
+    # the four-wavefront case, and the row-dot buffers are sized from it)
+    run_case(wl.small(variant, wl.BF16, B=1, NH=2, T=384, dqk=256, dhv=512, chunk=chunk, seed=43 + chunk), with_dCn=True)

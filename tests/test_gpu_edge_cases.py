@@ -161,3 +161,16 @@ def test_zero_batch_is_an_error_not_a_launch():
     import paper_2503_14376_amd as tfla
     assert tfla.check(0, 0, 8, 256, 64, 64, 64, 0, 1) == -2
     assert tfla.check(0, 1, 8, 0, 64, 64, 64, 0, 1) == -2
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
+@pytest.mark.parametrize("dqk,dhv,T", [(32, 32, 256), (96, 192, 320), (192, 80, 200), (8, 64, 128), (256, 384, 256)])
+def test_head_dimensions_between_the_kernel_widths(variant, dtype, dqk, dhv, T):
+    """Head dimensions that are not 64, 128, 256 or 512 (the paper's head-dimension benchmark starts at 32): forward
+    with an initial state, final state, backward -- everything as for the problem as given, 1/sqrt(dqk) of the true dqk
+    included."""
+    if dtype == wl.F32 and max(dqk, dhv) > 256:
+        pytest.skip("the fp32 path goes up to 256")
+    w = wl.small(variant, dtype, B=1, NH=2, T=T, dqk=dqk, dhv=dhv, chunk=64, seed=85 + dqk + dhv)
+    _fwd_bwd(w, wl.make_inputs(w))

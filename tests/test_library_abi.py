@@ -68,7 +68,7 @@ def test_check_accepts_the_benchmark_configurations(tfla):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(B=0), -2), (dict(NH=-1), -2), (dict(T=0), -2), (dict(dqk=96), -2), (dict(dhv=1024), -2),
+    (dict(B=0), -2), (dict(NH=-1), -2), (dict(T=0), -2), (dict(dqk=100), -2), (dict(dqk=4), -2), (dict(dhv=1024), -2),
     (dict(dtype=0, dhv=512), -2), (dict(B=4096, NH=16), -2),
     (dict(chunk=0), -3), (dict(chunk=32), -3), (dict(chunk=96), -3), (dict(chunk=4096), -3),
     (dict(T=64 * 8192, chunk=64), -3),
@@ -89,6 +89,15 @@ def test_ragged_sequence_lengths_are_accepted_and_need_more_workspace(tfla):
         ragged = tfla.workspace_bytes(direction, **dict(a, T=8192 - 1))
         # the same number of chunks plus padded copies of the inputs and per-step outputs
         assert ragged > whole + 16 * 8192 * (256 + 256 + 512) * 2
+
+
+def test_head_dimensions_between_the_kernel_widths_are_accepted(tfla):
+    # any multiple of 8 up to 512 runs zero-padded to the next width of the kernels, with more workspace
+    for dqk, dhv in ((32, 32), (96, 192), (8, 504)):
+        assert _check(tfla, dqk=dqk, dhv=dhv) == 0
+    a = dict(OK_ARGS); a.pop("direction")
+    for direction in (0, 1):
+        assert tfla.workspace_bytes(direction, **dict(a, dqk=192)) > tfla.workspace_bytes(direction, **a)
 
 
 def test_status_strings(tfla):
