@@ -174,3 +174,24 @@ def test_head_dimensions_between_the_kernel_widths(variant, dtype, dqk, dhv, T):
         pytest.skip("the fp32 path goes up to 256")
     w = wl.small(variant, dtype, B=1, NH=2, T=T, dqk=dqk, dhv=dhv, chunk=64, seed=85 + dqk + dhv)
     _fwd_bwd(w, wl.make_inputs(w))
+
+
+_SWEEP = [(dqk, dhv, chunk) for dqk in (64, 128, 256, 512) for dhv in (64, 128, 256, 512) for chunk in (64, 128, 192, 256)
+          if (dqk * 3 + dhv * 5 + chunk * 7) % 5 in (0, 2)]       # a fixed two-fifths of the 64 combinations
+
+
+@pytest.mark.parametrize("dqk,dhv,chunk", _SWEEP)
+def test_kernel_width_and_chunk_combinations(dqk, dhv, chunk):
+    """Every kernel width with every kind of chunk size (multiples of 128 take the four-wavefront workgroups and the
+    128-row pieces, the others the two-wavefront ones and 64-row pieces): forward with initial state and backward."""
+    variant = wl.EXP if (dqk + dhv + chunk) % 128 == 0 else wl.SIG
+    w = wl.small(variant, wl.BF16, B=1, NH=2, T=3 * chunk, dqk=dqk, dhv=dhv, chunk=chunk, seed=87 + dqk + dhv + chunk)
+    _fwd_bwd(w, wl.make_inputs(w))
+
+
+@pytest.mark.parametrize("dqk,dhv,chunk", [(64, 256, 64), (128, 64, 192), (256, 256, 128), (256, 128, 64), (64, 64, 256),
+                                           (128, 256, 192), (256, 64, 128)])
+def test_kernel_width_and_chunk_combinations_fp32(dqk, dhv, chunk):
+    variant = wl.EXP if (dqk + chunk) % 128 == 0 else wl.SIG
+    w = wl.small(variant, wl.F32, B=1, NH=2, T=2 * chunk, dqk=dqk, dhv=dhv, chunk=chunk, seed=89 + dqk + dhv + chunk)
+    _fwd_bwd(w, wl.make_inputs(w))
