@@ -11,6 +11,9 @@ namespace {
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// sequences longer than this take the anchored forget-gate gradient scan (see bwd_core)
+constexpr int ANCHOR_FROM_T = 8192;
+
 struct Dims {
     int B, NH, T, dqk, dhv, L, variant, dtype;   // T: whole chunks (the padded length when the caller's is ragged)
     long BH, BHT;
@@ -89,7 +92,7 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
 }
 
 struct BwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal, *anchor;
     double* bsum;
     void *cN, *dcT, *dcN, *E;
     int nbQ, nbK;
@@ -108,6 +111,7 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.nbK = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DK, d.L);
     w.partQ = c.take<float>((size_t)w.nbQ * d.BHT); w.partK = c.take<float>((size_t)w.nbK * d.BHT);
     w.cdot = c.take<float>(d.BH);
+    w.anchor = c.take<float>(d.BH * d.Nc);
     w.Cfinal = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
     const size_t st = (size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz;
     // bf16: C_{k-1} and dC_k, both as (d_hv, d_qk); fp32 additionally dC_k as (d_qk, d_hv)
@@ -332,6 +336,14 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
     gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
     gg.BHT = d.BHT; gg.bsum = w.bsum; gg.softcap = softcap;
+    gg.anchor = nullptr; gg.L = chunk; gg.Nc = d.Nc;
+    // Long sequences (bf16): the forget-gate scan is anchored at every chunk boundary with <C_k, dC_k>, whose
+    // cost (one more pass over both sets of chunk states) buys an error that no longer grows with sqrt(T).
+    if (tonly && d.T > ANCHOR_FROM_T) {
+        TFLA_LAUNCH(K_STATE_DOT, launch_chunk_anchors(cstates, w.dcT, dCn ? w.cdot : nullptr, w.anchor, d.Nc,
+                                                      (long)dqk * dhv, (int)d.BH, s));
+        gg.anchor = w.anchor;
+    }
     TFLA_LAUNCH(K_GATE_GRADS, launch_gate_grads(gg, (int)d.BH, s));
     return TFLA_OK;
 }

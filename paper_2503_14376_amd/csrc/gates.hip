@@ -311,7 +311,82 @@ __global__ void __launch_bounds__(256) gate_grads_kernel(GateGradArgs a) {
         }
     }
 }
+// The same with anchors.  The value of the reverse cumulative sum at a chunk boundary is known exactly:
+// the log forget gate of the first step of chunk k + 1 scales the boundary state C_{k+1} in every later
+// use, so d f-bar there is <C_{k+1}, dC_{k+1}>, which needs no summation over time.  Every chunk then
+// scans its own steps only, and rounding noise no longer accumulates over the whole sequence (it grows
+// with sqrt(T) in the unanchored scan).  One workgroup per chunk; a thread owns up to eight consecutive steps.
+__global__ void __launch_bounds__(256) gate_grads_anchored_kernel(GateGradArgs a) {
+    __shared__ double wt[4];
+    const int bh = blockIdx.y, kc = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long row = (long)bh * a.T;
+    const int SEG = (a.L + 255) / 256;                 // <= 8 for chunks up to 2048
+    const int l0 = tid * SEG;                          // first of this thread's steps within the chunk
+    float r[8], c[8];
+    double tot = 0.0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        r[e] = 0.0f; c[e] = 0.0f;
+        if (e < SEG && l0 + e < a.L) gate_grad_terms(a, row + (long)kc * a.L + l0 + e, r[e], c[e]);
+        tot += (double)r[e] - (double)c[e];
+    }
+    double x = tot;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { const double y = __shfl_down(x, o, 64); if (lane + o < 64) x += y; }
+    double excl = __shfl_down(x, 1, 64);
+    if (lane == 63) excl = 0.0;
+    if (lane == 0) wt[wave] = x;
+    __syncthreads();
+    for (int w = wave + 1; w < 4; ++w) excl += wt[w];
+    double run = excl + (double)a.anchor[(long)bh * a.Nc + kc];
+#pragma unroll
+    for (int e = 7; e >= 0; --e) {
+        if (e < SEG && l0 + e < a.L) {
+            const long t = (long)kc * a.L + l0 + e;
+            run += (double)r[e] - (double)c[e];
+            const float fp = a.f_pre[row + t], ip = a.i_pre[row + t];
+            a.d_f[row + t] = (float)run * sigmoid_neg(soft_cap(fp, a.softcap)) * soft_cap_grad(fp, a.softcap);
+            a.d_i[row + t] = (a.variant == 0 ? c[e] : c[e] * sigmoid_neg(soft_cap(ip, a.softcap))) * soft_cap_grad(ip, a.softcap);
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) chunk_anchors_kernel(const bf16_t* Cst, const bf16_t* dCst, const float* cdot,
+                                                            float* anchor, int Nc, long per) {
+    __shared__ double wt[4];
+    const int kc = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+    if (kc == Nc - 1) {
+        if (tid == 0) anchor[(long)bh * Nc + kc] = cdot ? cdot[bh] : 0.0f;
+        return;
+    }
+    const bf16_t* A = Cst + ((long)bh * Nc + kc + 1) * per;
+    const bf16_t* B = dCst + ((long)bh * Nc + kc) * per;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (long i = (long)tid * 8; i < per; i += 256 * 8) {
+        const u32x4 x = *reinterpret_cast<const u32x4*>(A + i), y = *reinterpret_cast<const u32x4*>(B + i);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            acc[e] += bf16_lo_to_f32(x[e]) * bf16_lo_to_f32(y[e]) + bf16_hi_to_f32(x[e]) * bf16_hi_to_f32(y[e]);
+    }
+    double tot = ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o, 64);
+    if ((tid & 63) == 0) wt[tid >> 6] = tot;
+    __syncthreads();
+    if (tid == 0) anchor[(long)bh * Nc + kc] = (float)((wt[0] + wt[1]) + (wt[2] + wt[3]));
+}
+hipError_t launch_chunk_anchors(const void* Cst, const void* dCst, const float* cdot, float* anchor, int Nc, long per,
+                                int BH, hipStream_t s) {
+    hipLaunchKernelGGL(chunk_anchors_kernel, dim3(Nc, BH), dim3(256), 0, s, reinterpret_cast<const bf16_t*>(Cst),
+                       reinterpret_cast<const bf16_t*>(dCst), cdot, anchor, Nc, per);
+    return hipGetLastError();
+}
+
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s) {
+    if (a.anchor) {
+        hipLaunchKernelGGL(gate_grads_anchored_kernel, dim3(a.Nc, BH), dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
     const dim3 grid((a.T + GG_BLOCK - 1) / GG_BLOCK, BH);
     hipLaunchKernelGGL(gate_grads_sum_kernel, grid, dim3(256), 0, s, a);
     hipError_t e = hipGetLastError();

@@ -44,6 +44,9 @@ struct GateGradArgs {
     double* bsum;                  // (BH, ceil(T / 1024)) scratch: block sums
     int T, variant; long BHT;
     float softcap;                 // as in GateArgs: the gradients are taken through the cap
+    // optional anchors of the reverse cumulative sum: anchor[bh][k] = its exact value just after the last step
+    // of chunk k (see launch_chunk_anchors); NULL = one scan over the whole sequence
+    const float* anchor; int L, Nc;
 };
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
 
@@ -55,6 +58,11 @@ hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, 
 hipError_t launch_pad_scalar(const float* in, float* out, long BH, int T, int Tp, float fill, hipStream_t s);
 hipError_t launch_unpad_scalar(const float* in, float* out, long BH, int T, int Tp, hipStream_t s);
 hipError_t launch_state_dot(const float* A, const float* Bm, float* out, long per, int BH, hipStream_t s);
+// anchor[bh][k] = <C_{k+1}, dC_{k+1}> for k < Nc - 1 (bf16 chunk states as the recurrent kernel stores them:
+// Cst[bh][k] is the state before chunk k, dCst[bh][k] the gradient of the state after chunk k), and
+// cdot[bh] (or 0) for the last chunk
+hipError_t launch_chunk_anchors(const void* Cst, const void* dCst, const float* cdot, float* anchor, int Nc, long per,
+                                int BH, hipStream_t s);
 
 // ---- single recurrent step (Sec. 2.1, Sec. 4.1) ------------------------------------------------
 struct StepArgs {

@@ -67,3 +67,11 @@ def test_bwd_wide_heads_with_chunks_that_are_not_multiples_of_128(variant, chunk
     # the 512-wide contraction of dQ / dK with the two-wavefront workgroups (their block width differs from
     # the four-wavefront case, and the row-dot buffers are sized from it)
     run_case(wl.small(variant, wl.BF16, B=1, NH=2, T=384, dqk=256, dhv=512, chunk=chunk, seed=43 + chunk), with_dCn=True)
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("T,dqk,dhv,chunk", [(16384, 64, 128, 128), (9000, 64, 64, 64), (12288, 128, 64, 2048)])
+def test_bwd_long_sequences_take_the_anchored_gate_scan(variant, T, dqk, dhv, chunk):
+    # beyond 8192 steps the forget-gate gradient is anchored at the chunk boundaries with <C_k, dC_k>
+    run_case(wl.small(variant, wl.BF16, B=1, NH=2, T=T, dqk=dqk, dhv=dhv, chunk=chunk, seed=47 + chunk), with_dCn=True,
+             oracle_chunk=256)
