@@ -40,7 +40,9 @@ int check_dims(int direction, int B, int NH, int T, int dqk, int dhv, int chunk,
     if (chunk < 64 || chunk > 2048 || chunk % 64 != 0) return TFLA_ERR_CHUNK;
     const int nc = (T + chunk - 1) / chunk;
     if (nc > 4096) return TFLA_ERR_CHUNK;
-    if ((long)B * NH * nc > 2147483647L / 2) return TFLA_ERR_SHAPE;
+    // workgroups of the largest tiled launch (one-dimensional grid): column blocks x row blocks x chunks x (batch*head)
+    const long dmx = kernel_dim(dqk > dhv ? dqk : dhv);
+    if ((long)B * NH * nc * (dmx / 64) * (chunk / 64) > 2147483647L) return TFLA_ERR_SHAPE;
     return TFLA_OK;
 }
 

@@ -46,13 +46,15 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     // XCD-aware decomposition of the workgroup id: the workgroups of one chunk (all d2 blocks
     // and row blocks, which share K/V/state tiles) are neighbours on one XCD.
-    const unsigned nwg = gridDim.x * gridDim.y * gridDim.z;
-    unsigned wg = xcd_remap(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), nwg);
-    const int nb2 = wg % gridDim.x; wg /= gridDim.x;
+    // one-dimensional launch (the number of workgroups can exceed what the y and z grid dimensions hold):
+    // linear id -> (column block, row block, chunk, batch*head), column blocks fastest
+    const unsigned nwg = gridDim.x, gx = (unsigned)a.d2 / BD2, gy = (unsigned)a.L / (32 * NW);
+    unsigned wg = xcd_remap(blockIdx.x, nwg);
+    const int nb2 = wg % gx; wg /= gx;
     // later row blocks of a lower-triangular kernel (earlier ones of an upper one) have more
     // column tiles: start them first
-    const int rbi = wg % gridDim.y; wg /= gridDim.y;
-    const int rb = UPPER ? rbi : (int)gridDim.y - 1 - rbi;
+    const int rbi = wg % gy; wg /= gy;
+    const int rb = UPPER ? rbi : (int)gy - 1 - rbi;
     const int kc = wg % a.Nc, bh = wg / a.Nc;
     const long tbase = (long)bh * a.T + (long)kc * a.L;   // first step of the chunk
     const int r0 = rb * BR;                               // chunk-local first row of the workgroup
@@ -236,7 +238,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
             for (int nb = 0; nb < NB; ++nb)
                 d += acc[nb][v] * E::to_f32(W[t * d2 + (long)nb2 * BD2 + nb * 32 + l32]);
             d = half_sum(d);
-            if (l32 == 0) a.dotpart[(long)nb2 * ((long)gridDim.z / a.Nc) * a.T + t] = d;
+            if (l32 == 0) a.dotpart[(long)nb2 * (long)(nwg / (gx * gy * (unsigned)a.Nc)) * a.T + t] = d;
         }
     }
 }
@@ -244,7 +246,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 // ------------------------------------------------------------------------------------------
 template <typename DT, int D1, int BD2, int NW, int MODE>
 static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
-    dim3 grid(a.d2 / BD2, a.L / (32 * NW), BH * a.Nc);
+    dim3 grid((unsigned)((long)(a.d2 / BD2) * (a.L / (32 * NW)) * BH * a.Nc));
     if constexpr (sizeof(DT) == 2) {
         // two workgroups per CU when the accumulator is narrow enough for 256 registers per lane
         constexpr int OCC = (BD2 <= 128 && D1 <= 256) ? 2 : 1;

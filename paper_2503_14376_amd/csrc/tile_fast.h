@@ -69,11 +69,13 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     TFLA_TL(0);
-    const unsigned nwg = gridDim.x * gridDim.y * gridDim.z;
-    unsigned wg = xcd_remap(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), nwg);
-    const int nb2 = __builtin_amdgcn_readfirstlane((int)(wg % gridDim.x)); wg /= gridDim.x;
-    const int rbi = __builtin_amdgcn_readfirstlane((int)(wg % gridDim.y)); wg /= gridDim.y;
-    const int rb = UPPER ? rbi : (int)gridDim.y - 1 - rbi;      // row blocks with more column tiles first
+    // one-dimensional launch (the number of workgroups can exceed what the y and z grid dimensions hold):
+    // linear id -> (column block, row block, chunk, batch*head), column blocks fastest
+    const unsigned nwg = gridDim.x, gx = (unsigned)a.d2 / BD2, gy = (unsigned)a.L / (32 * NW);
+    unsigned wg = xcd_remap(blockIdx.x, nwg);
+    const int nb2 = __builtin_amdgcn_readfirstlane((int)(wg % gx)); wg /= gx;
+    const int rbi = __builtin_amdgcn_readfirstlane((int)(wg % gy)); wg /= gy;
+    const int rb = UPPER ? rbi : (int)gy - 1 - rbi;      // row blocks with more column tiles first
     const int kc = __builtin_amdgcn_readfirstlane((int)(wg % a.Nc));
     const int bh = __builtin_amdgcn_readfirstlane((int)(wg / a.Nc));
     const long tbase = (long)bh * a.T + (long)kc * a.L;
@@ -482,7 +484,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
                      acc[nb][4 * j + 2] * bf16_lo_to_f32(w.y) + acc[nb][4 * j + 3] * bf16_hi_to_f32(w.y);
             }
         d += __shfl_xor(d, 32, 64);
-        if (g == 0) a.dotpart[(long)nb2 * ((long)gridDim.z / a.Nc) * a.T + t] = d;
+        if (g == 0) a.dotpart[(long)nb2 * (long)(nwg / (gx * gy * (unsigned)a.Nc)) * a.T + t] = d;
     }
     TFLA_TL(5);
 #ifdef TFLA_TIMELINE

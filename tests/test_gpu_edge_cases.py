@@ -195,3 +195,29 @@ def test_kernel_width_and_chunk_combinations_fp32(dqk, dhv, chunk):
     variant = wl.EXP if (dqk + chunk) % 128 == 0 else wl.SIG
     w = wl.small(variant, wl.F32, B=1, NH=2, T=2 * chunk, dqk=dqk, dhv=dhv, chunk=chunk, seed=89 + dqk + dhv + chunk)
     _fwd_bwd(w, wl.make_inputs(w))
+
+
+def test_more_than_65536_chunk_workgroup_groups():
+    """batch*head x chunks beyond what one grid dimension holds (the tiled kernels are launched on a one-dimensional
+    grid): the first and the last (batch, head) slice against the oracle, forward and backward."""
+    import paper_2503_14376_amd as tfla
+    from tests import gpu_util as gu
+    B, NH, T, d, chunk = 128, 8, 4096, 64, 64           # 1024 slices x 64 chunks = 65536
+    g = torch.Generator(device="cuda").manual_seed(4242)
+    bf = torch.bfloat16
+    mk = lambda *shape: torch.randn(shape, device="cuda", generator=g)
+    q, k, v, dH = (mk(B, NH, T, d).to(bf) for _ in range(4))
+    ip, fp = mk(B, NH, T), mk(B, NH, T) + 3.0
+    print("edge big grid", (B, NH, T, d, chunk), flush=True)
+    f = tfla.mlstm_fwd(q, k, v, ip, fp, chunk=chunk, variant=wl.EXP, eps=1e-6)
+    b = tfla.mlstm_bwd(q, k, v, ip, fp, dH, f["n_out"], f["m_out"], chunk=chunk, variant=wl.EXP, eps=1e-6,
+                       fwd_workspace=f["workspace"])
+    torch.cuda.synchronize()
+    for (bi, hi) in ((0, 0), (B - 1, NH - 1), (77, 3)):
+        sl = lambda t: t[bi, hi].float().cpu().numpy().astype(np.float64)[None]
+        ref = orc.recurrent_fwd(sl(q), sl(k), sl(v), sl(ip), sl(fp), variant=wl.EXP, eps=1e-6)
+        rb = orc.chunkwise_bwd(sl(q), sl(k), sl(v), sl(ip), sl(fp), sl(dH), variant=wl.EXP, eps=1e-6, chunk=256)
+        assert gu.rel_err(f["H"][bi, hi], ref["H"][0]) <= 2e-2
+        assert gu.rel_err(f["Cn"][bi, hi], ref["Cn"][0]) <= 2e-2
+        for key, rk in dict(dq="dq", dk="dk", dv="dv", d_i_pre="di", d_f_pre="df").items():
+            assert gu.rel_err(b[key][bi, hi], rb[rk][0]) <= 2e-2, (bi, hi, key)
