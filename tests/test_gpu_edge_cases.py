@@ -221,3 +221,33 @@ def test_more_than_65536_chunk_workgroup_groups():
         assert gu.rel_err(f["Cn"][bi, hi], ref["Cn"][0]) <= 2e-2
         for key, rk in dict(dq="dq", dk="dk", dv="dv", d_i_pre="di", d_f_pre="df").items():
             assert gu.rel_err(b[key][bi, hi], rb[rk][0]) <= 2e-2, (bi, hi, key)
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+def test_optional_outputs_may_be_omitted(variant):
+    """No final state, no n/m record, no dC0: through the C ABI with NULL pointers; what is produced equals the full call."""
+    import ctypes
+    import paper_2503_14376_amd as tfla
+    from paper_2503_14376_amd import binding as bd
+    from tests import gpu_util as gu
+    w = wl.small(variant, wl.BF16, B=1, NH=2, T=256, dqk=64, dhv=128, chunk=64, seed=95, init_state=False)
+    dev = gu.dev_inputs(w, wl.make_inputs(w))
+    full = tfla.mlstm_fwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], chunk=64, variant=variant)
+    gfull = tfla.mlstm_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["dH"], full["n_out"], full["m_out"],
+                           chunk=64, variant=variant)
+    lib = tfla.load_library()
+    P = bd._ptr
+    H = torch.empty_like(full["H"])
+    ws = torch.empty(tfla.workspace_bytes(0, 1, 2, 256, 64, 128, 64, variant, 1), dtype=torch.uint8, device="cuda")
+    rc = lib.tfla_mlstm_fwd(P(dev["q"]), P(dev["k"]), P(dev["v"]), P(dev["i_pre"]), P(dev["f_pre"]), None, None, None,
+                            1, 2, 256, 64, 128, 64, variant, 1, 1e-6, P(H), None, None, None, None, None,
+                            P(ws), ws.numel(), bd._stream_handle(None))
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert torch.equal(H, full["H"])
+    g = tfla.mlstm_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["dH"], full["n_out"], full["m_out"],
+                       chunk=64, variant=variant, want_dC0=False)
+    torch.cuda.synchronize()
+    assert "dC0" not in g
+    for key in ("dq", "dk", "dv", "d_i_pre", "d_f_pre"):
+        assert torch.equal(g[key], gfull[key]), key
