@@ -27,10 +27,10 @@
  *    nn, mn, n_out, m_out are filled with zeros when non-NULL.
  *  - eps is added to the denominator max{|n^T q~|, exp(-m)}; eps = 0 is the paper's formula.
  *  - Restrictions: chunk % 64 == 0, 64 <= chunk <= 2048, ceil(T / chunk) <= 4096, dqk and dhv
- *    multiples of 8, at most 512 (at most 256 for TFLA_F32),
+ *    multiples of 8, at most 1024 (at most 256 for TFLA_F32),
  *    B * NH <= 65535.
  *  - T need not be a multiple of chunk (N_c = ceil(T / chunk), Sec. 2.2), and the head dimensions need
- *    not be among the kernels' own widths 64, 128, 256, 512.  The kernels work on whole chunks and on
+ *    not be among the kernels' own widths 64, 128, 256, 512, 1024.  The kernels work on whole chunks and on
  *    those widths: otherwise the library copies the inputs into zero-padded buffers inside the workspace
  *    (which is correspondingly larger, see tfla_mlstm_workspace_bytes), gives the padding steps a forget
  *    gate of one and an input gate of zero, scales q by 1/sqrt of the true dqk, and copies the true part
@@ -139,7 +139,7 @@ TFLA_API int tfla_mlstm_bwd(const void* q, const void* k, const void* v,
  *        the same buffer as C (updated in place); n_out and m_out must be buffers different from
  *        n and m (they are read by every workgroup of a head) and are required for TFLA_EXP;
  *        for TFLA_SIG they are zero-filled when non-NULL.
- *   dqk, dhv: multiples of 64 in [64, 512]; B * NH <= 65535.  No workspace is needed.
+ *   dqk, dhv: multiples of 64 in [64, 1024]; B * NH <= 65535.  No workspace is needed.
  */
 TFLA_API int tfla_mlstm_step(const void* q, const void* k, const void* v,
                     const float* i_pre, const float* f_pre,

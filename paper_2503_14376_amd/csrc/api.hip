@@ -22,7 +22,7 @@ struct Dims {
 };
 
 // the head dimension the kernels run a caller's head dimension at (zero-padded columns in between)
-inline int kernel_dim(int d) { return d <= 64 ? 64 : (d <= 128 ? 128 : (d <= 256 ? 256 : 512)); }
+inline int kernel_dim(int d) { return d <= 64 ? 64 : (d <= 128 ? 128 : (d <= 256 ? 256 : (d <= 512 ? 512 : 1024))); }
 
 // core = true: the kernels' own widths only (what the kernel sequences are called with)
 int check_dims(int direction, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype, bool core = false) {
@@ -30,10 +30,10 @@ int check_dims(int direction, int B, int NH, int T, int dqk, int dhv, int chunk,
     if (variant != TFLA_EXP && variant != TFLA_SIG) return TFLA_ERR_ENUM;
     if (dtype != TFLA_F32 && dtype != TFLA_BF16) return TFLA_ERR_ENUM;
     if (B <= 0 || NH <= 0 || T <= 0 || dqk <= 0 || dhv <= 0) return TFLA_ERR_SHAPE;
-    const int dmax = dtype == TFLA_BF16 ? 512 : 256;
+    const int dmax = dtype == TFLA_BF16 ? 1024 : 256;
     auto ok_d = [&](int d) {
         if (d > dmax || d % 8 != 0) return false;
-        return !core || d == 64 || d == 128 || d == 256 || d == 512;
+        return !core || d == 64 || d == 128 || d == 256 || d == 512 || d == 1024;
     };
     if (!ok_d(dqk) || !ok_d(dhv)) return TFLA_ERR_SHAPE;
     if ((long)B * NH > 65535) return TFLA_ERR_SHAPE;
@@ -75,7 +75,7 @@ struct Carver {
 // chunk states C_{k-1} and the final state), so its layout is part of the library's contract
 // with itself: carve_fwd is the only place that defines it.
 struct FwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *nst, *Cfin;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *nst, *Cfin, *pacc, *pnrm;
     void* stT;
     size_t bytes;
 };
@@ -89,14 +89,17 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
     w.nst = c.take<float>(d.BH * d.Nc * d.dqk);
     w.Cfin = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
     w.stT = c.take_bytes((size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz);
+    // d_qk above 512: the parallel kernel contracts over d_qk in two halves that meet in fp32
+    w.pacc = d.dqk > 512 ? c.take<float>((size_t)d.BHT * d.dhv) : nullptr;
+    w.pnrm = d.dqk > 512 ? c.take<float>(d.BHT) : nullptr;
     w.bytes = c.off;
     return w;
 }
 
 struct BwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal, *anchor;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal, *anchor, *pacc;
     double* bsum;
-    void *cN, *dcT, *dcN, *E;
+    void *cN, *dcT, *dcN, *E, *E2;
     int nbQ, nbK;
     size_t bytes;
 };
@@ -121,6 +124,11 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.dcN = d.dtype == TFLA_BF16 ? nullptr : c.take_bytes(st);
     // bf16: the weighted intra-chunk matrix shared by dQ and dK, (BH, Nc, L, L)
     w.E = d.dtype == TFLA_BF16 ? c.take_bytes((size_t)d.BHT * d.L * d.esz) : nullptr;
+    // head dimensions above 512: fp32 partial results of the gradient kernels' first half, and the second
+    // half's E when the products of dQ / dK run over the halves of d_hv
+    const int dwide = d.dqk > d.dhv ? d.dqk : d.dhv;
+    w.pacc = dwide > 512 ? c.take<float>((size_t)d.BHT * dwide) : nullptr;
+    w.E2 = (d.dtype == TFLA_BF16 && d.dhv > 512) ? c.take_bytes((size_t)d.BHT * d.L * d.esz) : nullptr;
     w.bytes = c.off;
     return w;
 }
@@ -226,8 +234,9 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
 
     // 3. parallel kernel
-    TileArgs t;
+    TileArgs t{};
     t.X = q; t.Y = k; t.Z = v; t.Out = H;
+    t.part_acc = w.pacc; t.part_nrm = w.pnrm;
     t.wrow = w.wrow; t.wcol = w.ucol; t.srow = w.sH; t.St = w.stT;
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
     t.variant = variant; t.eps = eps; t.nstate = w.nst; t.mout = mout; t.nout = is_exp ? n_out : nullptr;
@@ -316,9 +325,9 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     TFLA_LAUNCH(K_REC_BWD, launch_recurrent(rb, (int)d.BH, dtype, s));
 
     // 4. the three gradient kernels
-    TileArgs t;
+    TileArgs t{};
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
-    t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr; t.E = w.E;
+    t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr; t.E = w.E; t.E2 = w.E2; t.part_acc = w.pacc;
     // dV: rows = kv index j
     t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = w.dcT;
     t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
@@ -352,7 +361,7 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
 
 // ---- sequence lengths that do not fill the last chunk, head dimensions between the kernels' own -------
-// The cores work on whole chunks and on head dimensions 64, 128, 256, 512.  For any other T or head
+// The cores work on whole chunks and on head dimensions 64, 128, 256, 512 (bf16 also 1024).  For any other T or head
 // dimension the entry points copy the inputs into zero-padded buffers behind the core's own workspace,
 // run the core there (Tvalid = T, the 1/sqrt(dqk) of the true dqk), and copy the true part of the outputs
 // back.  `d` below always describes the padded problem.
@@ -615,7 +624,7 @@ static int step_impl(const void* q, const void* k, const void* v, const float* i
     if (variant != TFLA_EXP && variant != TFLA_SIG) return TFLA_ERR_ENUM;
     if (dtype != TFLA_F32 && dtype != TFLA_BF16) return TFLA_ERR_ENUM;
     if (B <= 0 || NH <= 0 || (long)B * NH > 65535) return TFLA_ERR_SHAPE;
-    if (dqk < 64 || dqk > 512 || dqk % 64 != 0 || dhv < 64 || dhv > 512 || dhv % 64 != 0) return TFLA_ERR_SHAPE;
+    if (dqk < 64 || dqk > 1024 || dqk % 64 != 0 || dhv < 64 || dhv > 1024 || dhv % 64 != 0) return TFLA_ERR_SHAPE;
     if (!q || !k || !v || !i_pre || !f_pre || !C || !C_out || !h) return TFLA_ERR_NULL;
     if (variant == TFLA_EXP) {
         if ((n != nullptr) != (m != nullptr)) return TFLA_ERR_STATE;

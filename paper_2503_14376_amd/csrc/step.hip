@@ -16,7 +16,7 @@ namespace tfla {
 template <typename DT>
 __global__ void __launch_bounds__(256) step_kernel(StepArgs a) {
     using E = Elem<DT>;
-    __shared__ float sk[512], sq[512];
+    __shared__ float sk[1024], sq[1024];
     __shared__ float snum[16][64];
     __shared__ float sred[4];
     const int bh = blockIdx.y, nb = blockIdx.x, tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;

@@ -153,6 +153,14 @@ struct TileArgs {
     float* dotpart;                 // (d2/BD2, BH*T)
     // bf16 MODE_DQ writes, bf16 MODE_DK reads: the weighted matrix E of every chunk, (BH, Nc, L, L)
     void* E;
+    // Contraction widths above 512 (bf16): every term of the result is linear in the products over d1, so the
+    // launcher runs the kernel once per 512-wide half and the halves meet in fp32.  The caller provides the
+    // buffers; the remaining fields are filled in by the launcher.
+    float* part_acc;                // (BH, T, d2) unnormalised result of the first half
+    float* part_nrm;                // (BH, T) its share of the normaliser (MODE_H, mLSTMexp)
+    void* E2;                       // the second half's E (MODE_DQ writes, MODE_DK reads)
+    const float* acc_in; const float* nrm_in;   // add these to the accumulators / normaliser before the epilogue
+    float* acc_out; float* nrm_out;             // store the raw accumulators / normaliser instead of the output
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
 // d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16
@@ -163,6 +171,7 @@ template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int d
 // multiples of 128.)
 inline int tile_bd2(int d1, int d2, int dtype, int mode, int L) {
     if (dtype == 1 && (mode == MODE_DK || mode == MODE_DQ) && d1 == 512 && d2 % 256 == 0 && L % 128 == 0) return 256;
+    // (contractions over 1024 columns run as 512-wide halves with 128- or 64-wide blocks)
     if (d2 % 128 == 0) return 128;
     return 64;
 }

@@ -244,13 +244,13 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-template <typename DT, int D1, int BD2, int NW, int MODE>
+template <typename DT, int D1, int BD2, int NW, int MODE, int SPLIT = 0>
 static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
     dim3 grid((unsigned)((long)(a.d2 / BD2) * (a.L / (32 * NW)) * BH * a.Nc));
     if constexpr (sizeof(DT) == 2) {
         // two workgroups per CU when the accumulator is narrow enough for 256 registers per lane
         constexpr int OCC = (BD2 <= 128 && D1 <= 256) ? 2 : 1;
-        hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC>), grid, dim3(64 * NW), 0, s, a);
+        hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT>), grid, dim3(64 * NW), 0, s, a);
     } else {
         constexpr int BC = 32;   // two LDS stages must fit in 160 KB
         hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE>), grid, dim3(64 * NW), 0, s, a);
@@ -287,10 +287,47 @@ static hipError_t launch_tile_m(const TileArgs& a, int BH, int bd2, hipStream_t 
     return hipErrorInvalidValue;
 }
 
+// one 512-wide half (SPLIT = 1, 2) of a contraction over 1024 columns
+template <int MODE, int SPLIT>
+static hipError_t launch_tile_half(const TileArgs& a, int BH, int bd2, hipStream_t s) {
+    if (a.L % 128 == 0) {
+        if (bd2 == 128) return launch_tile_t<bf16_t, 512, 128, 4, MODE, SPLIT>(a, BH, s);
+        if (bd2 == 64) return launch_tile_t<bf16_t, 512, 64, 4, MODE, SPLIT>(a, BH, s);
+        return hipErrorInvalidValue;
+    }
+    if (bd2 == 128) return launch_tile_t<bf16_t, 512, 128, 2, MODE, SPLIT>(a, BH, s);
+    if (bd2 == 64) return launch_tile_t<bf16_t, 512, 64, 2, MODE, SPLIT>(a, BH, s);
+    return hipErrorInvalidValue;
+}
+
 template <int MODE>
-hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s) {
+hipError_t launch_tile_mode(const TileArgs& a0, int BH, int dtype, hipStream_t s) {
+    TileArgs a = a0;
+    a.acc_in = nullptr; a.nrm_in = nullptr; a.acc_out = nullptr; a.nrm_out = nullptr;
     const int bd2 = tile_bd2(a.d1, a.d2, dtype, MODE, a.L);
-    return dtype == 1 ? launch_tile_m<bf16_t, MODE>(a, BH, bd2, s) : launch_tile_m<float, MODE>(a, BH, bd2, s);
+    if (dtype != 1) return a.d1 > 256 ? hipErrorInvalidValue : launch_tile_m<float, MODE>(a, BH, bd2, s);
+    if (a.d1 <= 512) return launch_tile_m<bf16_t, MODE>(a, BH, bd2, s);
+    // d1 = 1024: the kernels hold a workgroup's X rows in registers, which ends at 512 columns.  Every term of
+    // the result is linear in the products over d1 (the weights depend on the gates only), so the contraction
+    // runs as two launches over 512 columns each: the first leaves its unnormalised accumulators (and its share
+    // of the normaliser) in fp32, the second adds them to its own before the epilogue.  dQ writes one matrix E
+    // per half (its products run over the halves of d_hv); dK reads the matching one in each of its launches.
+    constexpr bool STT = (MODE == MODE_DQ || MODE == MODE_DK);
+    const bool nrm = MODE == MODE_H && a.variant == 0;
+    if (a.d1 != 1024 || !a.part_acc || (nrm && !a.part_nrm) || (STT && a.E && !a.E2)) return hipErrorInvalidValue;
+    TileArgs h = a;
+    h.d1 = 512;
+    h.acc_out = a.part_acc; h.nrm_out = a.part_nrm;
+    hipError_t e = launch_tile_half<MODE, 1>(h, BH, bd2, s);
+    if (e != hipSuccess) return e;
+    h.acc_out = nullptr; h.nrm_out = nullptr;
+    h.acc_in = a.part_acc; h.nrm_in = a.part_nrm;
+    h.X = reinterpret_cast<const bf16_t*>(a.X) + 512;
+    if (MODE != MODE_DK) h.Y = reinterpret_cast<const bf16_t*>(a.Y) + 512;
+    h.St = reinterpret_cast<const bf16_t*>(a.St) + (STT ? (long)512 * a.d2 : 512);
+    if (a.nstate) h.nstate = a.nstate + 512;
+    if (STT) h.E = a.E2;
+    return launch_tile_half<MODE, 2>(h, BH, bd2, s);
 }
 
 // One translation unit per (mode, element type) keeps compile times parallel: tile_inst.hip

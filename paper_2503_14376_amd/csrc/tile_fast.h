@@ -26,7 +26,10 @@ static __device__ unsigned long long tfla_timeline[1 << 18];
 #define TFLA_TL(k)
 #endif
 
-template <int D1, int BD2, int NW, int MODE, int OCC>
+// SPLIT: 0 = the whole contraction over D1 in this launch; 1 / 2 = the first / second 512-wide half of a
+// contraction over 1024 columns (rows of the D1-wide operands are 2 D1 apart): the first half stores its raw fp32
+// accumulators, the second adds them to its own before the epilogue.
+template <int D1, int BD2, int NW, int MODE, int OCC, int SPLIT = 0>
 __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     using E = Elem<bf16_t>;
     using frag = E::frag;
@@ -81,29 +84,30 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     const long tbase = (long)bh * a.T + (long)kc * a.L;
     const int r0 = rb * BR, wr0 = r0 + wave * 32;
     const int d2 = a.d2;
+    constexpr int ld1 = SPLIT ? 2 * D1 : D1;    // row stride of the operands with D1 columns
 
     const bf16_t* X = reinterpret_cast<const bf16_t*>(a.X);
-    const bf16_t* Y = reinterpret_cast<const bf16_t*>(a.Y) + tbase * D1;
+    const bf16_t* Y = reinterpret_cast<const bf16_t*>(a.Y) + tbase * ld1;
     const bf16_t* Z = reinterpret_cast<const bf16_t*>(a.Z) + tbase * d2 + (long)nb2 * BD2;
     const bf16_t* St = reinterpret_cast<const bf16_t*>(a.St) +
-                       (STT ? ((long)bh * a.Nc + kc) * D1 * d2 + (long)nb2 * BD2
-                            : (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * D1);
+                       (STT ? ((long)bh * a.Nc + kc) * ld1 * d2 + (long)nb2 * BD2
+                            : (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * ld1);
 
     const int ct_lo = UPPER ? r0 / BC : 0;
     const int ct_hi = UPPER ? a.L / BC : (r0 + BR) / BC;
     const int NI = NPRE + (ct_hi - ct_lo);                      // items streamed through the ring
 
     using DS = typename std::conditional<STT, DmaTile<BCS, BD2, NT, SWZ_T>, DmaTile<BD2, BCS, NT, SWZ_K>>::type;
-    DS ds;  ds.init(STT ? d2 : D1, tid);
+    DS ds;  ds.init(STT ? d2 : ld1, tid);
     using DYT = typename std::conditional<ELITE, DmaTile<BC, BR, NT, SWZ_T>, DmaTile<BC, D1, NT, SWZ_K>>::type;
-    DYT dy;    dy.init(ELITE ? a.L : D1, tid);
+    DYT dy;    dy.init(ELITE ? a.L : ld1, tid);
     DmaTile<BC, BD2, NT, SWZ_T> dz;   dz.init(d2, tid);
     // E of this chunk: (L, L), rows = query index; the dK kernel reads the columns of its own rows
     const bf16_t* Eb = reinterpret_cast<const bf16_t*>(a.E) + ((long)bh * a.Nc + kc) * a.L * a.L + (ELITE ? r0 : 0);
     constexpr int CS = DS::N;
-    DmaTile<BR, BXS, NT, SWZ_K> dxs;  dxs.init(D1, tid);
+    DmaTile<BR, BXS, NT, SWZ_K> dxs;  dxs.init(ld1, tid);
     constexpr int CX = DmaTile<BR, BXS, NT, SWZ_K>::N;
-    const bf16_t* Xb = X + (tbase + r0) * D1;
+    const bf16_t* Xb = X + (tbase + r0) * ld1;
     constexpr int CT = DYT::N + DmaTile<BC, BD2, NT, SWZ_T>::N + (ELITE ? 0 : 1);
     const uint32_t smem_a = lds_addr(smem), w_a = lds_addr(ldsW);
     const float* wcol = a.wcol + tbase;
@@ -121,7 +125,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
                 dy.issue(Eb + (long)ct * BC * a.L, st, tid);
                 dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
             } else {
-                dy.issue(Y + (long)ct * BC * D1, st, tid);
+                dy.issue(Y + (long)ct * BC * ld1, st, tid);
                 dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
                 // the tile's 32 column weights (both half-waves fetch the same 32 floats)
                 dma4(wcol + ct * BC, (uint32_t)(lane & 31) * 4u, w_a + (uint32_t)(((item % NS) * NW + wave) * 256));
@@ -142,7 +146,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
                 dy.issue_part(Eb + (long)ct * BC * a.L, st, tid, part, nparts);
                 dz.issue_part(Z + (long)ct * BC * d2, st + YB, tid, part, nparts);
             } else {
-                dy.issue_part(Y + (long)ct * BC * D1, st, tid, part, nparts);
+                dy.issue_part(Y + (long)ct * BC * ld1, st, tid, part, nparts);
                 dz.issue_part(Z + (long)ct * BC * d2, st + YB, tid, part, nparts);
                 if (part == 0)
                     dma4(wcol + ct * BC, (uint32_t)(lane & 31) * 4u, w_a + (uint32_t)(((item % NS) * NW + wave) * 256));
@@ -168,7 +172,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             if (a.variant == 0) {
                 dma4(a.mout + tbase + wr0, vo, lds_addr(&ldsM[wave][0]));
                 for (int c = wave; c < D1 / 64; c += NW)
-                    dma4(a.nstate + ((long)bh * a.Nc + kc) * D1 + 64 * c, (uint32_t)lane * 4u, lds_addr(&ldsN[64 * c]));
+                    dma4(a.nstate + ((long)bh * a.Nc + kc) * ld1 + 64 * c, (uint32_t)lane * 4u, lds_addr(&ldsN[64 * c]));
             }
         }
     }
@@ -430,11 +434,45 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     TFLA_TL(4);
     // ---------------- epilogue
     const long t = tbase + wr0 + l32;       // this lane's output row
-    float inv = 1.0f;
     if (MODE == MODE_H) {
         if (a.variant == 0) {
             rowsum += __shfl_xor(rowsum, 32, 64);
             nrm += rowsum;
+        }
+    }
+    // One half of a contraction wider than D1: register quad 4j..4j+3 of block nb holds columns
+    // 32 nb + 8 j + 4 g + {0..3} of row t, so the fp32 partial results move as 16-byte accesses.
+    if constexpr (SPLIT == 2) {
+        const float* pin = a.acc_in + t * d2 + (long)nb2 * BD2 + 4 * g;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const f32x4 w = *reinterpret_cast<const f32x4*>(pin + 32 * nb + 8 * j);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[nb][4 * j + e] += w[e];
+            }
+            asm volatile("" ::: "memory");      // one block's loads at a time: no register pile-up
+        }
+        if (MODE == MODE_H && a.variant == 0) nrm += a.nrm_in[t];
+    }
+    if constexpr (SPLIT == 1) {
+        float* pout = a.acc_out + t * d2 + (long)nb2 * BD2 + 4 * g;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = acc[nb][4 * j + e];
+                *reinterpret_cast<f32x4*>(pout + 32 * nb + 8 * j) = w;
+            }
+        if (MODE == MODE_H && a.variant == 0 && g == 0 && nb2 == 0) a.nrm_out[t] = nrm;
+        return;
+    }
+    float inv = 1.0f;
+    if (MODE == MODE_H) {
+        if (a.variant == 0) {
             const float den = fmaxf(fabsf(nrm), expf(-ldsM[wave][l32])) + a.eps;
             inv = 1.0f / den;
             if (g == 0 && a.nout && nb2 == 0) a.nout[t] = nrm;

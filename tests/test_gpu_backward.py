@@ -70,6 +70,13 @@ def test_bwd_wide_heads_with_chunks_that_are_not_multiples_of_128(variant, chunk
 
 
 @pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("dqk,dhv", [(1024, 1024), (256, 1024), (1024, 128)])
+def test_bwd_head_dimensions_above_512_with_upstream_state_gradient(variant, dqk, dhv):
+    # contractions over 1024 columns run as two 512-wide launches; dC_T given, so <C_T, dC_T> and dC_0 are covered
+    run_case(wl.small(variant, wl.BF16, B=1, NH=1, T=512, dqk=dqk, dhv=dhv, chunk=128, seed=45 + dqk // 64 + dhv), with_dCn=True)
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
 @pytest.mark.parametrize("T,dqk,dhv,chunk", [(16384, 64, 128, 128), (9000, 64, 64, 64), (12288, 128, 64, 2048)])
 def test_bwd_long_sequences_take_the_anchored_gate_scan(variant, T, dqk, dhv, chunk):
     # beyond 8192 steps the forget-gate gradient is anchored at the chunk boundaries with <C_k, dC_k>

@@ -251,3 +251,20 @@ def test_optional_outputs_may_be_omitted(variant):
     assert "dC0" not in g
     for key in ("dq", "dk", "dv", "d_i_pre", "d_f_pre"):
         assert torch.equal(g[key], gfull[key]), key
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("dqk,dhv,chunk", [(1024, 1024, 256), (1024, 1024, 64), (512, 1024, 128), (1024, 256, 192),
+                                           (64, 1024, 64), (1024, 64, 256)])
+def test_head_dimensions_up_to_1024(variant, dqk, dhv, chunk):
+    """Head dimensions above 512 (the head-dimension benchmark of App. E.3 ends at 1024): the tiled kernels contract
+    over a 1024-wide dimension in two halves that meet in fp32; initial state given, so that every term is present."""
+    w = wl.small(variant, wl.BF16, B=1, NH=2, T=576 if chunk == 192 else 512, dqk=dqk, dhv=dhv, chunk=chunk,
+                 seed=300 + dqk // 64 + dhv // 8 + chunk)
+    _fwd_bwd(w, wl.make_inputs(w))
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+def test_head_dimensions_between_512_and_1024_and_ragged_length(variant):
+    w = wl.small(variant, wl.BF16, B=1, NH=1, T=300, dqk=520, dhv=1000, chunk=128, seed=411)
+    _fwd_bwd(w, wl.make_inputs(w))

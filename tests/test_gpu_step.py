@@ -18,7 +18,7 @@ def _dev(a, bf16):
 
 @pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
 @pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
-@pytest.mark.parametrize("dims", [(64, 64), (128, 192), (256, 512), (512, 512)])
+@pytest.mark.parametrize("dims", [(64, 64), (128, 192), (256, 512), (512, 512), (1024, 1024), (1024, 64)])
 def test_step_chain_matches_recurrence(variant, dtype, dims):
     import paper_2503_14376_amd as tfla
     from tests import gpu_util as gu

@@ -68,7 +68,7 @@ def test_check_accepts_the_benchmark_configurations(tfla):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(B=0), -2), (dict(NH=-1), -2), (dict(T=0), -2), (dict(dqk=100), -2), (dict(dqk=4), -2), (dict(dhv=1024), -2),
+    (dict(B=0), -2), (dict(NH=-1), -2), (dict(T=0), -2), (dict(dqk=100), -2), (dict(dqk=4), -2), (dict(dhv=1032), -2), (dict(dqk=2048), -2),
     (dict(dtype=0, dhv=512), -2), (dict(B=4096, NH=16), -2),
     (dict(chunk=0), -3), (dict(chunk=32), -3), (dict(chunk=96), -3), (dict(chunk=4096), -3),
     (dict(T=64 * 8192, chunk=64), -3),
@@ -92,8 +92,8 @@ def test_ragged_sequence_lengths_are_accepted_and_need_more_workspace(tfla):
 
 
 def test_head_dimensions_between_the_kernel_widths_are_accepted(tfla):
-    # any multiple of 8 up to 512 runs zero-padded to the next width of the kernels, with more workspace
-    for dqk, dhv in ((32, 32), (96, 192), (8, 504)):
+    # any multiple of 8 up to 1024 runs zero-padded to the next width of the kernels, with more workspace
+    for dqk, dhv in ((32, 32), (96, 192), (8, 504), (1024, 1024), (520, 1000)):
         assert _check(tfla, dqk=dqk, dhv=dhv) == 0
     a = dict(OK_ARGS); a.pop("direction")
     for direction in (0, 1):
@@ -178,7 +178,7 @@ def test_step_argument_validation_happens_before_any_launch(tfla):
     assert call(h=0) == -1
     assert call(n_out=0) == -1                     # the exponential-gate step returns n and m
     assert call(dqk=96) == -2
-    assert call(dhv=1024) == -2
+    assert call(dhv=2048) == -2
     assert call(B=0) == -2
     assert call(variant=3) == -4
     assert call(dtype=2) == -4
