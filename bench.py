@@ -74,11 +74,11 @@ def algorithmic_bytes(w: wl.Workload, es: int):
 # --calibrate-copy, each scaled by what the same counter reads for the 1 GiB copy kernel
 # (profiles/hbm_traffic_c4.txt).  Reported as roofline.traffic only for that workload.
 MEASURED_TRAFFIC_C4 = {
-    "recurrent_kernel": 216.4e6 + 148.1e6,
+    "recurrent_kernel": 217.9e6 + 148.1e6,
     "tile_kernel<H>": 405.4e6 + 134.7e6,
-    "tile_kernel<dV>": 406.9e6 + 134.2e6,
-    "tile_kernel<dQ>": 538.9e6 + 106.4e6,
-    "tile_kernel<dK>": 454.9e6 + 67.6e6,
+    "tile_kernel<dV>": 407.1e6 + 134.2e6,
+    "tile_kernel<dQ>": 538.9e6 + 106.8e6,
+    "tile_kernel<dK>": 454.8e6 + 67.6e6,
 }
 
 
