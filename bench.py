@@ -165,6 +165,8 @@ def main() -> int:
     ap.add_argument("--head-dim", type=int, default=0,
                     help="head-dimension sweep point of App. E.3: dqk = dhv = this value, NH = 4096 / value, B = 4 "
                          "(unless --batch), T = 8192; a secondary line")
+    ap.add_argument("--tile-width", type=int, default=0,
+                    help="tile-size sweep: output-column block of the tiled kernels (64 or 128; 0 = the library's choice)")
     ap.add_argument("--fwd-only", action="store_true")
     ap.add_argument("--recompute", action="store_true",
                     help="do not hand the forward workspace to the backward call (gates and chunk states are recomputed)")
@@ -193,6 +195,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     tfla.load_library()   # fails loudly if the HIP library is missing
+    if args.tile_width:
+        tfla.tile_width(args.tile_width)
     if args.workload == "step":
         return step_bench(args)
 
@@ -365,7 +369,7 @@ def main() -> int:
         "launch": "eager" if graph is None else "hip graph replay",
         "config": {"workload": w.name, "variant": "mLSTMexp" if w.variant == wl.EXP else "mLSTMsig",
                    "B": w.B, "NH": w.NH, "T": w.T, "dqk": w.dqk, "dhv": w.dhv, "chunk": w.chunk,
-                   "pass": ("layer " if args.layer else "") + ("fwd+bwd" if do_bwd else "fwd"), "states": "element type of q/k/v (bf16), fp32 accumulation"},
+                   "tile_width": args.tile_width or "auto", "pass": ("layer " if args.layer else "") + ("fwd+bwd" if do_bwd else "fwd"), "states": "element type of q/k/v (bf16), fp32 accumulation"},
         "algorithmic_tflops": total_fl / 1e12,
         "mfma_frac_of_peak_whole_step": total_fl / (ms_per_step * 1e-3) / peak,
         "roofline": roof,

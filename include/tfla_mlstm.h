@@ -265,6 +265,16 @@ TFLA_API int tfla_profile_enable(int max_launches);
 TFLA_API int tfla_profile_read(int kernel, char* name, int name_len, double* total_ms, long* launches);
 TFLA_API int tfla_profile_kernels(void);
 
+/*
+ * Measurement aid for tile-size sweeps (Sec. 3: the kernels' tile sizes are free parameters of the method; host
+ * function, process-wide state, not thread-safe): width of the output-column block of the bf16 tiled kernels.
+ * 0 (default) = chosen per kernel and shape; 64 or 128 = that width wherever it divides the tiled dimension;
+ * 256 = same as 0 (256-wide blocks are already taken wherever they are built).  Results do not depend on it;
+ * workspace layouts do, so set it before tfla_mlstm_workspace_bytes and keep it for the calls that use that
+ * workspace.  Returns TFLA_OK or TFLA_ERR_ENUM.
+ */
+TFLA_API int tfla_tile_width(int width);
+
 /* Library version, major * 1000 + minor. */
 TFLA_API int tfla_version(void);
 

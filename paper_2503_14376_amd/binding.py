@@ -17,7 +17,7 @@ _lib = None
 EXPORTS = ("tfla_mlstm_fwd", "tfla_mlstm_bwd", "tfla_mlstm_step", "tfla_mlstm_workspace_bytes", "tfla_mlstm_check",
            "tfla_status_string", "tfla_version", "tfla_profile_enable", "tfla_profile_read",
            "tfla_profile_kernels", "tfla_mlstm_layer_fwd", "tfla_mlstm_layer_bwd", "tfla_mlstm_layer_workspace_bytes",
-           "tfla_transfer_gain", "tfla_mlstm_layer_step")
+           "tfla_transfer_gain", "tfla_mlstm_layer_step", "tfla_tile_width")
 
 
 class TflaError(RuntimeError):
@@ -75,6 +75,8 @@ def load_library():
     lib.tfla_profile_read.argtypes = [ci, ctypes.c_char_p, ci, ctypes.POINTER(ctypes.c_double),
                                       ctypes.POINTER(ctypes.c_long)]
     lib.tfla_profile_kernels.restype = ci
+    lib.tfla_tile_width.restype = ci
+    lib.tfla_tile_width.argtypes = [ci]
     _lib = lib
     return lib
 
@@ -93,6 +95,13 @@ def layer_workspace_bytes(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) 
 
 def check(direction, B, NH, T, dqk, dhv, chunk, variant, dtype) -> int:
     return int(load_library().tfla_mlstm_check(direction, B, NH, T, dqk, dhv, chunk, variant, dtype))
+
+
+def tile_width(width: int) -> None:
+    """Output-column block of the bf16 tiled kernels for tile-size sweeps: 0 = automatic, 64, 128 (256 = automatic)."""
+    rc = load_library().tfla_tile_width(int(width))
+    if rc != 0:
+        raise TflaError(rc, "tfla_tile_width")
 
 
 def profile_enable(max_launches: int) -> None:

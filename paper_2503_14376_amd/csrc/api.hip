@@ -7,6 +7,8 @@
 
 using namespace tfla;
 
+namespace tfla { int tile_width_override = 0; }
+
 namespace {
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -534,7 +536,13 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
 
 extern "C" {
 
-int tfla_version(void) { return 1100; }
+int tfla_version(void) { return 1200; }
+
+int tfla_tile_width(int width) {
+    if (width != 0 && width != 64 && width != 128 && width != 256) return TFLA_ERR_ENUM;
+    tfla::tile_width_override = width;
+    return TFLA_OK;
+}
 
 int tfla_profile_enable(int max_launches) {
     if (g_prof.beg) {

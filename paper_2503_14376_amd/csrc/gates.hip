@@ -206,7 +206,10 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_step_kernel(GateArgs a)
 
 hipError_t launch_gates(const GateArgs& a, int BH, hipStream_t s) {
     const dim3 grid((a.Nc + GATE_WAVES - 1) / GATE_WAVES, BH);
+    // the log gates of a lane's steps stay in registers for every chunk size the library accepts (L <= 2048)
     if (a.L / 64 <= 8) hipLaunchKernelGGL(gates_chunk_kernel<8>, grid, dim3(GATE_WAVES * 64), 0, s, a);
+    else if (a.L / 64 <= 16) hipLaunchKernelGGL(gates_chunk_kernel<16>, grid, dim3(GATE_WAVES * 64), 0, s, a);
+    else if (a.L / 64 <= 32) hipLaunchKernelGGL(gates_chunk_kernel<32>, grid, dim3(GATE_WAVES * 64), 0, s, a);
     else hipLaunchKernelGGL(gates_chunk_kernel<0>, grid, dim3(GATE_WAVES * 64), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

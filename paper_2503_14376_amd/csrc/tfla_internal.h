@@ -169,7 +169,14 @@ template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int d
 // workgroups fetch the same X rows and column tiles, and dQ computes S once per 256 columns.
 // (The 256-wide instantiations exist for the four-wavefront workgroups only, i.e. for chunk sizes that are
 // multiples of 128.)
+// tile_width_override (set through tfla_tile_width, a measurement aid for tile-size sweeps): 0 = the choice
+// described above; 64 / 128 force that width wherever it divides d2; 256 changes nothing (it is already taken
+// wherever it is built).  The workspace layout depends on the width, so it must not change between the
+// workspace query, the forward call and the backward call of one step.
+extern int tile_width_override;
 inline int tile_bd2(int d1, int d2, int dtype, int mode, int L) {
+    const int ov = tile_width_override;
+    if (dtype == 1 && (ov == 64 || ov == 128) && d2 % ov == 0) return ov;
     if (dtype == 1 && (mode == MODE_DK || mode == MODE_DQ) && d1 == 512 && d2 % 256 == 0 && L % 128 == 0) return 256;
     // (contractions over 1024 columns run as 512-wide halves with 128- or 64-wide blocks)
     if (d2 % 128 == 0) return 128;

@@ -268,3 +268,16 @@ def test_head_dimensions_up_to_1024(variant, dqk, dhv, chunk):
 def test_head_dimensions_between_512_and_1024_and_ragged_length(variant):
     w = wl.small(variant, wl.BF16, B=1, NH=1, T=300, dqk=520, dhv=1000, chunk=128, seed=411)
     _fwd_bwd(w, wl.make_inputs(w))
+
+
+@pytest.mark.parametrize("width", [64, 128])
+def test_tile_width_override_gives_the_same_results(width):
+    """The tile-size sweep's knob: every block width the kernels are built with gives results within tolerance, at the
+    benchmark's head shape (where the automatic choice is 128 for H / dV and 256 for dQ / dK)."""
+    import paper_2503_14376_amd as tfla
+    w = wl.small(wl.EXP, wl.BF16, B=1, NH=2, T=512, dqk=256, dhv=512, chunk=256, seed=97)
+    tfla.tile_width(width)
+    try:
+        _fwd_bwd(w, wl.make_inputs(w))
+    finally:
+        tfla.tile_width(0)

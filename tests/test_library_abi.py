@@ -256,3 +256,20 @@ def test_layer_step_argument_validation(tfla):
     assert call(norm=3) == -4
     assert call(cap=-2.0) == -2
     assert call(dqk=100) == -2
+
+
+def test_tile_width_override_changes_workspace_layout_not_validity(tfla):
+    lib = tfla.load_library()
+    assert lib.tfla_tile_width(96) == -4 and lib.tfla_tile_width(-1) == -4
+    a = dict(OK_ARGS); a.pop("direction")
+    try:
+        auto = tfla.workspace_bytes(1, **a)
+        assert lib.tfla_tile_width(64) == 0
+        narrow = tfla.workspace_bytes(1, **a)
+        # narrower column blocks: more partial row-dot buffers (one per block of the dQ / dK kernels)
+        assert narrow > auto
+        assert lib.tfla_tile_width(256) == 0
+        assert tfla.workspace_bytes(1, **a) == auto
+    finally:
+        assert lib.tfla_tile_width(0) == 0
+    assert tfla.workspace_bytes(1, **a) == auto
