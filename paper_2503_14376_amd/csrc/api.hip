@@ -246,10 +246,13 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     TFLA_LAUNCH(K_TILE_H, launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
 
     if (!is_exp) {
-        if (nn) TFLA_LAUNCH(K_FILL, launch_fill_zero(nn, d.BH * dqk, s));
-        if (mn) TFLA_LAUNCH(K_FILL, launch_fill_zero(mn, d.BH, s));
-        if (n_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(n_out, d.BHT, s));
-        if (m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(m_out, d.BHT, s));
+        // the outputs that mLSTMsig does not have, zero-filled in one launch
+        FillList fl{};
+        if (nn) { fl.p[0] = nn; fl.n[0] = d.BH * dqk; }
+        if (mn) { fl.p[1] = mn; fl.n[1] = d.BH; }
+        if (n_out) { fl.p[2] = n_out; fl.n[2] = d.BHT; }
+        if (m_out) { fl.p[3] = m_out; fl.n[3] = d.BHT; }
+        if (nn || mn || n_out || m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero4(fl, s));
     }
     return TFLA_OK;
 }
@@ -647,8 +650,10 @@ static int step_impl(const void* q, const void* k, const void* v, const float* i
     a.h = h; a.dqk = dqk; a.dhv = dhv; a.variant = variant; a.dtype = dtype; a.eps = eps; a.softcap = softcap;
     TFLA_LAUNCH(K_STEP, launch_step(a, B * NH, s));
     if (variant == TFLA_SIG) {
-        if (n_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(n_out, (long)B * NH * dqk, s));
-        if (m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero(m_out, (long)B * NH, s));
+        FillList fl{};
+        if (n_out) { fl.p[0] = n_out; fl.n[0] = (long)B * NH * dqk; }
+        if (m_out) { fl.p[1] = m_out; fl.n[1] = (long)B * NH; }
+        if (n_out || m_out) TFLA_LAUNCH(K_FILL, launch_fill_zero4(fl, s));
     }
     return TFLA_OK;
 }

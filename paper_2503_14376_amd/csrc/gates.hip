@@ -408,6 +408,26 @@ hipError_t launch_fill_zero(float* p, long n, hipStream_t s) {
     return hipGetLastError();
 }
 
+// up to four arrays in one launch: element i of the concatenation belongs to the first array whose end lies beyond i
+__global__ void __launch_bounds__(256) fill_zero4_kernel(FillList f) {
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (i < f.n[q]) { f.p[q][i] = 0.0f; return; }
+        i -= f.n[q];
+    }
+}
+hipError_t launch_fill_zero4(const FillList& f, hipStream_t s) {
+    long total = 0;
+    for (int q = 0; q < 4; ++q) {
+        if (f.n[q] < 0 || (f.n[q] > 0 && !f.p[q])) return hipErrorInvalidValue;
+        total += f.n[q];
+    }
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, f);
+    return hipGetLastError();
+}
+
 // out[bh] = <A[bh], B[bh]> over `per` floats
 __global__ void __launch_bounds__(1024) state_dot_kernel(const float* A, const float* Bm, float* out, long per) {
     __shared__ double wt[16];

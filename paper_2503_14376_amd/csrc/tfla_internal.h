@@ -51,6 +51,8 @@ struct GateGradArgs {
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
 
 hipError_t launch_fill_zero(float* p, long n, hipStream_t s);
+struct FillList { float* p[4]; long n[4]; };     // n[q] = 0: slot unused
+hipError_t launch_fill_zero4(const FillList& f, hipStream_t s);
 // (BH, T, row) <-> (BH, Tp, row_p) copies for sequence lengths that are not a multiple of the chunk and head
 // dimensions between the supported ones (pad.hip); row bytes multiples of 16, pointers 16-byte aligned
 hipError_t launch_pad_rows(const void* in, void* out, long BH, int T, int Tp, int row_bytes, int row_bytes_p, hipStream_t s);

@@ -281,3 +281,31 @@ def test_tile_width_override_gives_the_same_results(width):
         _fwd_bwd(w, wl.make_inputs(w))
     finally:
         tfla.tile_width(0)
+
+
+def test_sigmoid_variant_zero_fills_the_outputs_it_does_not_have():
+    """mLSTMsig has no normaliser and no max state: nn, mn, n_out, m_out come back as zeros (one fill launch for
+    all of them), whatever the buffers held before; likewise n and m of the generation step."""
+    import paper_2503_14376_amd as tfla
+    from tests import gpu_util as gu
+    w = wl.small(wl.SIG, wl.BF16, B=2, NH=3, T=192, dqk=64, dhv=128, chunk=64, seed=99)
+    dev = gu.dev_inputs(w, wl.make_inputs(w))
+    call = lambda out: tfla.mlstm_fwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev.get("C0"), None, None,
+                                      chunk=w.chunk, variant=w.variant, eps=1e-6, out=out)
+    out = {}
+    call(out)
+    for key in ("nn", "mn", "n_out", "m_out"):
+        out[key].fill_(float("nan"))
+    call(out)
+    torch.cuda.synchronize()
+    for key in ("nn", "mn", "n_out", "m_out"):
+        assert float(out[key].abs().max()) == 0.0, key
+    s = tfla.mlstm_step(dev["q"][:, :, 0].contiguous(), dev["k"][:, :, 0].contiguous(), dev["v"][:, :, 0].contiguous(),
+                        dev["i_pre"][:, :, 0].contiguous(), dev["f_pre"][:, :, 0].contiguous(), out["Cn"], None, None,
+                        variant=w.variant)
+    s["n"].fill_(float("nan")); s["m"].fill_(float("nan"))
+    s2 = tfla.mlstm_step(dev["q"][:, :, 0].contiguous(), dev["k"][:, :, 0].contiguous(), dev["v"][:, :, 0].contiguous(),
+                         dev["i_pre"][:, :, 0].contiguous(), dev["f_pre"][:, :, 0].contiguous(), out["Cn"], None, None,
+                         variant=w.variant, out=s)
+    torch.cuda.synchronize()
+    assert float(s2["n"].abs().max()) == 0.0 and float(s2["m"].abs().max()) == 0.0
