@@ -13,8 +13,8 @@ namespace {
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// sequences longer than this take the anchored forget-gate gradient scan (see bwd_core)
-constexpr int ANCHOR_FROM_T = 8192;
+// chunks between the anchors of the forget-gate gradient scan (see bwd_core)
+constexpr int ANCHOR_CHUNKS = 4;
 
 struct Dims {
     int B, NH, T, dqk, dhv, L, variant, dtype;   // T: whole chunks (the padded length when the caller's is ragged)
@@ -352,11 +352,14 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
     gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
     gg.BHT = d.BHT; gg.bsum = w.bsum; gg.softcap = softcap;
-    gg.anchor = nullptr; gg.L = chunk; gg.Nc = d.Nc;
-    // Long sequences (bf16): the forget-gate scan is anchored at every chunk boundary with <C_k, dC_k>, whose
-    // cost (one more pass over both sets of chunk states) buys an error that no longer grows with sqrt(T).
-    if (tonly && d.T > ANCHOR_FROM_T) {
-        TFLA_LAUNCH(K_STATE_DOT, launch_chunk_anchors(cstates, w.dcT, dCn ? w.cdot : nullptr, w.anchor, d.Nc,
+    gg.anchor = nullptr; gg.L = chunk; gg.Nc = d.Nc; gg.G = 1;
+    // bf16: the forget-gate scan is anchored with <C_k, dC_k> at the end of every block of ANCHOR_CHUNKS chunks
+    // (fewer when the chunks are long: a block has at most 2048 steps), so that the rounding noise of its terms
+    // (one part in 2^9 of the boundary terms per chunk, from the bf16 states) accumulates over one block
+    // instead of the whole sequence; the cost is one read of both states at every block boundary.
+    if (tonly) {
+        gg.G = ANCHOR_CHUNKS * chunk <= 2048 ? ANCHOR_CHUNKS : (2048 / chunk > 0 ? 2048 / chunk : 1);
+        TFLA_LAUNCH(K_STATE_DOT, launch_chunk_anchors(cstates, w.dcT, dCn ? w.cdot : nullptr, w.anchor, d.Nc, gg.G,
                                                       (long)dqk * dhv, (int)d.BH, s));
         gg.anchor = w.anchor;
     }

@@ -316,21 +316,25 @@ __global__ void __launch_bounds__(256) gate_grads_kernel(GateGradArgs a) {
 }
 // The same with anchors.  The value of the reverse cumulative sum at a chunk boundary is known exactly:
 // the log forget gate of the first step of chunk k + 1 scales the boundary state C_{k+1} in every later
-// use, so d f-bar there is <C_{k+1}, dC_{k+1}>, which needs no summation over time.  Every chunk then
-// scans its own steps only, and rounding noise no longer accumulates over the whole sequence (it grows
-// with sqrt(T) in the unanchored scan).  One workgroup per chunk; a thread owns up to eight consecutive steps.
+// use, so d f-bar there is <C_{k+1}, dC_{k+1}>, which needs no summation over time.  Every block of G chunks
+// then scans its own steps only, from the anchor at its end, and the rounding noise of the terms no longer
+// accumulates over the whole sequence (it grows with sqrt(T) in the unanchored scan).  One workgroup per
+// block (at most 2048 steps); a thread owns up to eight consecutive steps.
 __global__ void __launch_bounds__(256) gate_grads_anchored_kernel(GateGradArgs a) {
     __shared__ double wt[4];
-    const int bh = blockIdx.y, kc = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bh = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long row = (long)bh * a.T;
-    const int SEG = (a.L + 255) / 256;                 // <= 8 for chunks up to 2048
-    const int l0 = tid * SEG;                          // first of this thread's steps within the chunk
+    const int kc0 = blk * a.G, kc1 = min(kc0 + a.G, a.Nc);      // chunks [kc0, kc1)
+    const long tb = (long)kc0 * a.L;                            // first step of the block
+    const int len = (kc1 - kc0) * a.L;                          // steps in this block
+    const int SEG = (a.G * a.L + 255) / 256;           // <= 8: G * L <= 2048
+    const int l0 = tid * SEG;                          // first of this thread's steps within the block
     float r[8], c[8];
     double tot = 0.0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         r[e] = 0.0f; c[e] = 0.0f;
-        if (e < SEG && l0 + e < a.L) gate_grad_terms(a, row + (long)kc * a.L + l0 + e, r[e], c[e]);
+        if (e < SEG && l0 + e < len) gate_grad_terms(a, row + tb + l0 + e, r[e], c[e]);
         tot += (double)r[e] - (double)c[e];
     }
     double x = tot;
@@ -341,11 +345,14 @@ __global__ void __launch_bounds__(256) gate_grads_anchored_kernel(GateGradArgs a
     if (lane == 0) wt[wave] = x;
     __syncthreads();
     for (int w = wave + 1; w < 4; ++w) excl += wt[w];
-    double run = excl + (double)a.anchor[(long)bh * a.Nc + kc];
+    // the anchor at the end of the block arrives in one partial sum per chunk of the block
+    double anc = 0.0;
+    for (int s_ = kc0; s_ < kc1; ++s_) anc += (double)a.anchor[(long)bh * a.Nc + s_];
+    double run = excl + anc;
 #pragma unroll
     for (int e = 7; e >= 0; --e) {
-        if (e < SEG && l0 + e < a.L) {
-            const long t = (long)kc * a.L + l0 + e;
+        if (e < SEG && l0 + e < len) {
+            const long t = tb + l0 + e;
             run += (double)r[e] - (double)c[e];
             const float fp = a.f_pre[row + t], ip = a.i_pre[row + t];
             a.d_f[row + t] = (float)run * sigmoid_neg(soft_cap(fp, a.softcap)) * soft_cap_grad(fp, a.softcap);
@@ -354,18 +361,26 @@ __global__ void __launch_bounds__(256) gate_grads_anchored_kernel(GateGradArgs a
     }
 }
 
+// Anchor of every block of G chunks: <C, dC> at the block's end (cdot at the end of the sequence).  The product
+// over the `per` state elements is split between as many workgroups as the block has chunks; workgroup s
+// leaves its partial sum in the anchor slot of the block's chunk s, and the scan adds the slots of its block.
 __global__ void __launch_bounds__(256) chunk_anchors_kernel(const bf16_t* Cst, const bf16_t* dCst, const float* cdot,
-                                                            float* anchor, int Nc, long per) {
+                                                            float* anchor, int Nc, int G, long per) {
     __shared__ double wt[4];
-    const int kc = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+    const int kc0 = (int)blockIdx.x * G, kc1 = min(kc0 + G, Nc), nsl = kc1 - kc0, sl = blockIdx.z;
+    const int bh = blockIdx.y, tid = threadIdx.x;
+    if (sl >= nsl) return;
+    const int kc = kc1 - 1;                          // the block ends after chunk kc
+    float* out = anchor + (long)bh * Nc + kc0 + sl;
     if (kc == Nc - 1) {
-        if (tid == 0) anchor[(long)bh * Nc + kc] = cdot ? cdot[bh] : 0.0f;
+        if (tid == 0) *out = (sl == 0 && cdot) ? cdot[bh] : 0.0f;
         return;
     }
     const bf16_t* A = Cst + ((long)bh * Nc + kc + 1) * per;
     const bf16_t* B = dCst + ((long)bh * Nc + kc) * per;
+    const long lo = (per / 8 * sl / nsl) * 8, hi = (per / 8 * (sl + 1) / nsl) * 8;     // 16-byte aligned slices
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (long i = (long)tid * 8; i < per; i += 256 * 8) {
+    for (long i = lo + (long)tid * 8; i < hi; i += 256 * 8) {
         const u32x4 x = *reinterpret_cast<const u32x4*>(A + i), y = *reinterpret_cast<const u32x4*>(B + i);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -376,18 +391,20 @@ __global__ void __launch_bounds__(256) chunk_anchors_kernel(const bf16_t* Cst, c
     for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o, 64);
     if ((tid & 63) == 0) wt[tid >> 6] = tot;
     __syncthreads();
-    if (tid == 0) anchor[(long)bh * Nc + kc] = (float)((wt[0] + wt[1]) + (wt[2] + wt[3]));
+    if (tid == 0) *out = (float)((wt[0] + wt[1]) + (wt[2] + wt[3]));
 }
-hipError_t launch_chunk_anchors(const void* Cst, const void* dCst, const float* cdot, float* anchor, int Nc, long per,
+hipError_t launch_chunk_anchors(const void* Cst, const void* dCst, const float* cdot, float* anchor, int Nc, int G, long per,
                                 int BH, hipStream_t s) {
-    hipLaunchKernelGGL(chunk_anchors_kernel, dim3(Nc, BH), dim3(256), 0, s, reinterpret_cast<const bf16_t*>(Cst),
-                       reinterpret_cast<const bf16_t*>(dCst), cdot, anchor, Nc, per);
+    if (G < 1 || G > 64 || per % 8 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(chunk_anchors_kernel, dim3((Nc + G - 1) / G, BH, G), dim3(256), 0, s, reinterpret_cast<const bf16_t*>(Cst),
+                       reinterpret_cast<const bf16_t*>(dCst), cdot, anchor, Nc, G, per);
     return hipGetLastError();
 }
 
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s) {
     if (a.anchor) {
-        hipLaunchKernelGGL(gate_grads_anchored_kernel, dim3(a.Nc, BH), dim3(256), 0, s, a);
+        if (a.G < 1 || (long)a.G * a.L > 2048) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(gate_grads_anchored_kernel, dim3((a.Nc + a.G - 1) / a.G, BH), dim3(256), 0, s, a);
         return hipGetLastError();
     }
     const dim3 grid((a.T + GG_BLOCK - 1) / GG_BLOCK, BH);

@@ -62,7 +62,7 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
     constexpr int CPC = DY::N;                      // loads per consumer and piece (Y)
     constexpr int NST = 4;                          // state stores per consumer at a chunk boundary
     constexpr int STEADY = (NS - 2) * CPP, STEADY_C = (NS - 2) * CPC;
-    static_assert(STEADY + NH + 1 <= 63 && STEADY_C + (NH + 1) * NST <= 63, "wait counts must fit the 6-bit counter");
+    static_assert(STEADY + 2 * (NH + 1) <= 63 && STEADY_C + (NH + 1) * NST <= 63, "wait counts must fit the 6-bit counter");
     static_assert(CPC % KS == 0, "Y requests are spread evenly over the k steps");
 
     __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
@@ -194,12 +194,18 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
             // published; emit n before that chunk, then apply the chunk
             if (n_owner && sub == PPC - 1) {
                 const int kc = a.reverse ? a.Nc - 1 - step : step;
-                a.nst[((long)bh * a.Nc + kc) * a.d1 + m0 + lane] = nacc;
+                // n before this chunk leaves as two bf16 rows of d1: the rounded value and the rounding
+                // remainder (together good to 2^-17), the form in which the parallel kernel feeds it to the
+                // matrix unit next to the state
+                uint16_t* np = reinterpret_cast<uint16_t*>(a.nst) + ((long)bh * a.Nc + kc) * 2 * a.d1 + m0 + lane;
+                const uint32_t nhi = bf16_bits_rne(nacc);
+                np[0] = (uint16_t)nhi;
+                np[a.d1] = (uint16_t)bf16_bits_rne(nacc - bf16_lo_to_f32(nhi));
                 float s = 0.0f;
 #pragma unroll
                 for (int w = 0; w < WN; ++w) s += ldsNx[step & 1][w][lane];
                 nacc = ldsG[slot][lane] * nacc + s;
-                st0 = 1;
+                st0 = 2;
             }
             if (i + NS - 1 < P) request();
             TFLA_RTL(4 * i + 1);

@@ -44,9 +44,10 @@ struct GateGradArgs {
     double* bsum;                  // (BH, ceil(T / 1024)) scratch: block sums
     int T, variant; long BHT;
     float softcap;                 // as in GateArgs: the gradients are taken through the cap
-    // optional anchors of the reverse cumulative sum: anchor[bh][k] = its exact value just after the last step
-    // of chunk k (see launch_chunk_anchors); NULL = one scan over the whole sequence
-    const float* anchor; int L, Nc;
+    // optional anchors of the reverse cumulative sum, one per block of G chunks (G * L <= 2048): its exact value
+    // just after the last step of the block, as the sum of the anchor slots of the block's chunks (see
+    // launch_chunk_anchors); NULL = one scan over the whole sequence
+    const float* anchor; int L, Nc, G;
 };
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
 
@@ -60,10 +61,11 @@ hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, 
 hipError_t launch_pad_scalar(const float* in, float* out, long BH, int T, int Tp, float fill, hipStream_t s);
 hipError_t launch_unpad_scalar(const float* in, float* out, long BH, int T, int Tp, hipStream_t s);
 hipError_t launch_state_dot(const float* A, const float* Bm, float* out, long per, int BH, hipStream_t s);
-// anchor[bh][k] = <C_{k+1}, dC_{k+1}> for k < Nc - 1 (bf16 chunk states as the recurrent kernel stores them:
-// Cst[bh][k] is the state before chunk k, dCst[bh][k] the gradient of the state after chunk k), and
-// cdot[bh] (or 0) for the last chunk
-hipError_t launch_chunk_anchors(const void* Cst, const void* dCst, const float* cdot, float* anchor, int Nc, long per,
+// For every block of G chunks ending after chunk k: <C_{k+1}, dC_{k+1}> (bf16 chunk states as the recurrent
+// kernel stores them: Cst[bh][k] is the state before chunk k, dCst[bh][k] the gradient of the state after
+// chunk k), or cdot[bh] (or 0) at the end of the sequence, left as partial sums in the anchor slots
+// anchor[bh][first chunk of the block ...] (one per chunk of the block)
+hipError_t launch_chunk_anchors(const void* Cst, const void* dCst, const float* cdot, float* anchor, int Nc, int G, long per,
                                 int BH, hipStream_t s);
 
 // ---- single recurrent step (Sec. 2.1, Sec. 4.1) ------------------------------------------------
@@ -129,7 +131,8 @@ struct RecArgs {
     float* Sfinal;        // (BH, d1, d2) fp32 or NULL
     float* Sfinal2;       // second copy of the final state, or NULL
     const float* n0;      // (BH, d1) or NULL; normaliser vector, forward mLSTMexp only
-    float* nst;           // (BH, Nc, d1) or NULL (NULL = no normaliser vector)
+    float* nst;           // (BH, Nc, d1) or NULL (NULL = no normaliser vector); the bf16 kernel stores the same
+                          // bytes as (BH, Nc, 2, d1) bf16: n rounded to bf16, and the rounding remainder
     float* nfinal;        // (BH, d1) or NULL
     int T, L, Nc, d1, d2, reverse;
 };
@@ -147,7 +150,7 @@ struct TileArgs {
     int T, L, Nc, d1, d2;
     // MODE_H, mLSTMexp: normaliser
     int variant; float eps;
-    const float* nstate;            // (BH, Nc, d1)
+    const float* nstate;            // (BH, Nc, d1); bf16 kernels: (BH, Nc, 2, d1) bf16 as RecArgs::nst
     const float* mout;              // (BH, T)
     float* nout;                    // (BH, T) or NULL
     // MODE_DQ / MODE_DK: partial row dots  sum_n out[r,n] * dotwith[r,n]

@@ -325,7 +325,8 @@ hipError_t launch_tile_mode(const TileArgs& a0, int BH, int dtype, hipStream_t s
     h.X = reinterpret_cast<const bf16_t*>(a.X) + 512;
     if (MODE != MODE_DK) h.Y = reinterpret_cast<const bf16_t*>(a.Y) + 512;
     h.St = reinterpret_cast<const bf16_t*>(a.St) + (STT ? (long)512 * a.d2 : 512);
-    if (a.nstate) h.nstate = a.nstate + 512;
+    // (n_{k-1} is stored as bf16 rows: 512 columns are 1024 bytes)
+    if (a.nstate) h.nstate = reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.nstate) + 1024);
     if (STT) h.E = a.E2;
     return launch_tile_half<MODE, 2>(h, BH, bd2, s);
 }

@@ -171,8 +171,20 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         if (MODE == MODE_H) {
             if (a.variant == 0) {
                 dma4(a.mout + tbase + wr0, vo, lds_addr(&ldsM[wave][0]));
-                for (int c = wave; c < D1 / 64; c += NW)
-                    dma4(a.nstate + ((long)bh * a.Nc + kc) * ld1 + 64 * c, (uint32_t)lane * 4u, lds_addr(&ldsN[64 * c]));
+                // n_{k-1}: two bf16 rows (rounded value, rounding remainder) of ld1 columns per chunk; the rows
+                // are contiguous when this launch covers all their columns
+                const char* nsrc = reinterpret_cast<const char*>(a.nstate) + ((long)bh * a.Nc + kc) * ld1 * 4;
+                if constexpr (SPLIT == 0) {
+                    for (int c = wave; c < D1 / 64; c += NW)
+                        dma4(nsrc + 256 * c, (uint32_t)lane * 4u, lds_addr(ldsN) + 256u * c);
+                } else {
+                    constexpr int PR = D1 / 128;        // 256-byte loads per row
+                    for (int c = wave; c < 2 * PR; c += NW) {
+                        const int r = c / PR, cc = c % PR;
+                        dma4(nsrc + (long)r * ld1 * 2 + 256 * cc, (uint32_t)lane * 4u,
+                             lds_addr(ldsN) + (uint32_t)(r * D1 * 2 + 256 * cc));
+                    }
+                }
             }
         }
     }
@@ -273,20 +285,24 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     float nrm = 0.0f;
     if (MODE == MODE_H) {
         if (a.variant == 0) {
-            // q~ . n_{k-1} from the X fragments in registers: eight consecutive n per fragment (two 16-byte
-            // LDS reads), four partial sums to shorten the dependency chain
-            float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            // q~ . n_{k-1} on the matrix unit: n sits in LDS as two bf16 rows (value, remainder), which enter as
+            // rows 0 and 1 of an otherwise empty 32-row operand next to the X fragments in registers; the
+            // two result columns of a row add up to its dot product
+            f32x16 an;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) an[v] = 0.0f;
+            const char* nrow = reinterpret_cast<const char*>(ldsN) + (l32 & 1) * (D1 * 2) + 16 * g;
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks) {
-                const f32x4 n0 = *reinterpret_cast<const f32x4*>(&ldsN[16 * ks + 8 * g]);
-                const f32x4 n1 = *reinterpret_cast<const f32x4*>(&ldsN[16 * ks + 8 * g + 4]);
-                const u32x4 w = __builtin_bit_cast(u32x4, xf[ks].v);
-                d4[0] += bf16_lo_to_f32(w[0]) * n0[0] + bf16_hi_to_f32(w[0]) * n0[1];
-                d4[1] += bf16_lo_to_f32(w[1]) * n0[2] + bf16_hi_to_f32(w[1]) * n0[3];
-                d4[2] += bf16_lo_to_f32(w[2]) * n1[0] + bf16_hi_to_f32(w[2]) * n1[1];
-                d4[3] += bf16_lo_to_f32(w[3]) * n1[2] + bf16_hi_to_f32(w[3]) * n1[3];
+                frag bn;
+                bn.v = *reinterpret_cast<const bf16x8*>(nrow + 32 * ks);
+                if (l32 >= 2) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) bn.v[e] = (bf16_t)0.0f;
+                }
+                an = E::mma(bn, xf[ks], an);
             }
-            float dot = (d4[0] + d4[1]) + (d4[2] + d4[3]);
+            float dot = g == 0 ? an[0] + an[1] : 0.0f;
             dot += __shfl_xor(dot, 32, 64);
             nrm = dot * srl;
         }

@@ -79,6 +79,7 @@ def test_bwd_head_dimensions_above_512_with_upstream_state_gradient(variant, dqk
 @pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
 @pytest.mark.parametrize("T,dqk,dhv,chunk", [(16384, 64, 128, 128), (9000, 64, 64, 64), (12288, 128, 64, 2048)])
 def test_bwd_long_sequences_take_the_anchored_gate_scan(variant, T, dqk, dhv, chunk):
-    # beyond 8192 steps the forget-gate gradient is anchored at the chunk boundaries with <C_k, dC_k>
+    # the forget-gate gradient scan is anchored with <C_k, dC_k> every few chunks: its error must not grow with T
+    # (blocks of four chunks, of one chunk at L = 2048, and a last block that is not full at T = 9000)
     run_case(wl.small(variant, wl.BF16, B=1, NH=2, T=T, dqk=dqk, dhv=dhv, chunk=chunk, seed=47 + chunk), with_dCn=True,
              oracle_chunk=256)
