@@ -26,6 +26,7 @@ import workloads as wl  # noqa: E402
 PEAK_BF16_MFMA = 2.5e15     # FLOP/s, MI355X dense bf16 (no sparsity)
 PEAK_FP32_MFMA = 157.3e12   # FLOP/s, MI355X fp32 matrix
 PEAK_HBM = 8.0e12           # B/s
+DEFAULT_CHUNK = 256          # chunk size of the headline workload (c4)
 
 
 def algorithmic_flops(w: wl.Workload, F_causal: float = 0.5):
@@ -69,17 +70,32 @@ def algorithmic_bytes(w: wl.Workload, es: int):
     }
 
 
-# HBM bytes per launch (fetched + written) of each kernel at the default workload (c4, chunk 256,
-# exponential gate), from rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script with
-# --calibrate-copy, each scaled by what the same counter reads for the 1 GiB copy kernel
-# (profiles/hbm_traffic_c4.txt).  Reported as roofline.traffic only for that workload.
-MEASURED_TRAFFIC_C4 = {
-    "recurrent_kernel": 217.9e6 + 148.1e6,
-    "tile_kernel<H>": 405.4e6 + 134.7e6,
-    "tile_kernel<dV>": 407.1e6 + 134.2e6,
-    "tile_kernel<dQ>": 538.9e6 + 106.8e6,
-    "tile_kernel<dK>": 454.8e6 + 67.6e6,
-}
+def profiled_traffic():
+    """HBM bytes per launch (fetched + written) of each kernel at the default workload (c4, chunk 256,
+    exponential gate), read from the committed summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+    script (profiles/hbm_traffic_c4.txt, column total_MB; the counters are scaled there by what they read for a
+    1 GiB copy kernel).  A figure from that profile, not a measurement of the present run: the bench line labels it
+    so.  Returns {} when the file is absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_c4.txt")
+    modes = {"0": "tile_kernel<H>", "1": "tile_kernel<dV>", "2": "tile_kernel<dQ>", "3": "tile_kernel<dK>"}
+    out = {}
+    try:
+        for line in open(path):
+            f = line.split()
+            try:
+                total = float(f[-1]) * 1e6
+            except (IndexError, ValueError):
+                continue
+            if line.startswith("recurrent_kernel_bf16"):
+                out["recurrent_kernel"] = total
+            elif line.startswith("tile_kernel_bf16<"):
+                # template arguments <D1, BD2, NW, MODE, ...>
+                targs = line[line.index("<") + 1:line.index(">")].replace(" ", "").split(",")
+                if len(targs) >= 4 and targs[3] in modes:
+                    out[modes[targs[3]]] = total
+    except OSError:
+        pass
+    return out
 
 
 def step_bench(args) -> int:
@@ -189,7 +205,6 @@ def main() -> int:
 
     import torch
     import paper_2503_14376_amd as tfla
-    from tests import gpu_util as gu
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -214,7 +229,7 @@ def main() -> int:
     if do_bwd and not w.backward:
         w = dataclasses.replace(w, backward=True)
     d = wl.make_layer_inputs(w) if args.layer else wl.make_inputs(w)
-    dev = {key: gu.to_dev(val, w.dtype if key in ("q", "k", "v", "dH", "o_pre") else wl.F32) for key, val in d.items()}
+    dev = {key: wl.to_dev(val, w.dtype if key in ("q", "k", "v", "dH", "o_pre") else wl.F32) for key, val in d.items()}
     torch.cuda.synchronize()
 
     f32 = torch.float32
@@ -328,14 +343,15 @@ def main() -> int:
         # the roofline that binds a kernel is the one with the larger floor time
         hbm_bound = pd["bytes"] / PEAK_HBM > pd["flops"] / peak
         traffic = None
-        if (w.name, w.chunk, w.variant) == ("c4", 256, wl.EXP) and dom in MEASURED_TRAFFIC_C4:
-            traffic = MEASURED_TRAFFIC_C4[dom]
+        if (w.name, w.chunk, w.variant) == ("c4", DEFAULT_CHUNK, wl.EXP):
+            traffic = profiled_traffic().get(dom)
         roof = {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom,
                 "achieved": pd["gbs"] if hbm_bound else pd["tflops"],
                 "peak": PEAK_HBM / 1e9 if hbm_bound else peak / 1e12,
                 "unit": "GB/s" if hbm_bound else "TFLOP/s",
                 "frac": pd["hbm_frac"] if hbm_bound else pd["mfma_frac"],
                 "traffic": traffic,
+                "traffic_source": "profiles/hbm_traffic_c4.txt (rocprofv3 --pmc runs of this command, not this run)" if traffic else None,
                 "avg_launch_ms": pd["avg_ms"], "algorithmic_bytes_per_launch": pd["bytes"],
                 "algorithmic_flops_per_launch": pd["flops"],
                 "kernels": {k_: {m_: (round(x_, 5) if isinstance(x_, float) and x_ < 1e6 else x_) for m_, x_ in v_.items()}
@@ -347,11 +363,11 @@ def main() -> int:
         from oracle import mlstm_oracle as orc
         nsl = min(16, w.B * w.NH)
         ds = wl.make_inputs(w, heads=nsl)
-        oi = gu.oracle_inputs(ds)
+        oi = wl.oracle_inputs(ds)
         c0 = time.perf_counter()
         orc.recurrent_fwd(**oi, variant=w.variant, eps=1e-6)
         if do_bwd:
-            orc.chunkwise_bwd(**oi, dH=gu.flat(ds["dH"]), variant=w.variant, eps=1e-6, chunk=w.chunk)
+            orc.chunkwise_bwd(**oi, dH=wl.flat(ds["dH"]), variant=w.variant, eps=1e-6, chunk=w.chunk)
         c1 = time.perf_counter()
         frac = nsl / float(w.B * w.NH)
         cpu = {"value": tokens * frac / (c1 - c0), "unit": "tokens/s", "cores": int(orc.num_threads()),
@@ -361,8 +377,8 @@ def main() -> int:
                                                                    " + fp64 chunkwise backward (numpy)" if do_bwd else "")}
 
     line = {
-        "metric": ("mLSTM fwd+bwd tokens/s and % bf16 MFMA peak at T=8192, NH=8, dqk=256, dhv=512" if do_bwd
-                   else "mLSTM fwd tokens/s"),
+        "metric": "mLSTM %s tokens/s and %% %s MFMA peak at T=%d, NH=%d, dqk=%d, dhv=%d" % (
+            "fwd+bwd" if do_bwd else "fwd", "bf16" if w.dtype == wl.BF16 else "fp32", w.T, w.NH, w.dqk, w.dhv),
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == wl.BF16 else "f32", "data": "synthetic",
@@ -370,7 +386,7 @@ def main() -> int:
         "config": {"workload": w.name, "variant": "mLSTMexp" if w.variant == wl.EXP else "mLSTMsig",
                    "B": w.B, "NH": w.NH, "T": w.T, "dqk": w.dqk, "dhv": w.dhv, "chunk": w.chunk,
                    "tile_width": args.tile_width or "auto", "pass": ("layer " if args.layer else "") + ("fwd+bwd" if do_bwd else "fwd"), "states": "element type of q/k/v (bf16), fp32 accumulation"},
-        "algorithmic_tflops": total_fl / 1e12,
+        "algorithmic_tflop_per_step": total_fl / 1e12,
         "mfma_frac_of_peak_whole_step": total_fl / (ms_per_step * 1e-3) / peak,
         "roofline": roof,
         "cpu_baseline": cpu,

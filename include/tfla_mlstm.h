@@ -36,6 +36,11 @@
  *    gate of one and an input gate of zero, scales q by 1/sqrt of the true dqk, and copies the true part
  *    of the results back, so the result is that of the problem as given; tensor and state pointers must
  *    then be 16-byte aligned (TFLA_ERR_SHAPE).
+ *  - Global state: the compute entry points keep none (their only shared data is the read-only table of
+ *    kernel instantiations).  The two measurement aids at the end of this file, per-kernel timing
+ *    (tfla_profile_*) and the tile-width override (tfla_tile_width), are process-wide, mutable and not
+ *    thread-safe: they exist for benchmarks and tests and must not be changed while another thread is
+ *    inside the library.  A program that never calls them gets the stateless library.
  *  - Return value: TFLA_OK (0) on success; a negative TFLA_ERR_* code for an invalid
  *    argument (checked before anything is launched, nothing is written); a positive value is
  *    the hipError_t of a failed launch.  No entry point throws or aborts.

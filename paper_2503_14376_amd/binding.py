@@ -393,5 +393,5 @@ def transfer_gain(h, v, norm_kind=NORM_RMS, norm_eps=1e-6, stream=None):
     rc = lib.tfla_transfer_gain(_ptr(h), _ptr(v), B, NH, T, dhv, dtype, int(norm_kind), float(norm_eps), _ptr(gb), _ptr(ga),
                                 _stream_handle(stream))
     if rc != 0:
-        raise TflaError(rc, "tfla_transfer_gain", "tfla_mlstm_layer_step")
+        raise TflaError(rc, "tfla_transfer_gain")
     return gb, ga

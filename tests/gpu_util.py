@@ -8,27 +8,8 @@ import workloads as wl
 TOL = {wl.BF16: 2e-2, wl.F32: 1e-4}   # max |gpu - ref| / max |ref| per output tensor
 
 
-def to_dev(a, dtype):
-    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    return t.to(torch.bfloat16) if dtype == wl.BF16 else t      # inputs are bf16-representable: exact
-
-
-def dev_inputs(w, d):
-    out = {}
-    for key, val in d.items():
-        out[key] = to_dev(val, w.dtype if key in ("q", "k", "v", "dH") else wl.F32)
-    return out
-
-
-def flat(a):
-    """(B, NH, ...) -> (B*NH, ...) float64 for the oracle."""
-    a = np.asarray(a, dtype=np.float64)
-    return a.reshape((a.shape[0] * a.shape[1],) + a.shape[2:])
-
-
-def oracle_inputs(d):
-    keys = ("q", "k", "v", "i_pre", "f_pre", "C0", "n0", "m0")
-    return {k_: (flat(d[k_]) if k_ in d else None) for k_ in keys}
+# moving workloads to the device and to the oracle's layout lives with the input generators
+to_dev, dev_inputs, flat, oracle_inputs = wl.to_dev, wl.dev_inputs, wl.flat, wl.oracle_inputs
 
 
 def rel_err(gpu, ref):

@@ -11,6 +11,8 @@ L5  transfer gains: what Sec. 4.1 states about Fig. "transfer behavior": the gai
     passes (about 1) or suppresses (about 0) depending on the input gate, mLSTMsig behaves like
     mLSTMexp, and a larger norm epsilon moves the transition towards larger input gate values
 """
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -160,6 +162,27 @@ def _gains(variant, i_val, f_val, norm_eps=1e-6, T=128, d=32, seed=21):
                           variant=variant, eps=0.0)
     gb, ga = lo.transfer_gain(o["H"][None], v, lo.RMS, norm_eps)
     return float(gb[0, 0]), float(ga[0, 0])
+
+
+def test_l5_gain_worked_by_hand():
+    """Gain equation of Sec. 4.1 on two steps of two columns, worked by hand: the ratio of max-norms is formed at
+    every step and then averaged.  h = [[1, -2], [3, 0.5]], v = [[2, 1], [1, -4]]:
+      before the norm: (2/2 + 3/4) / 2 = 0.875           (the ratio of the averages would be 2.5/3 = 0.8333)
+      RMS norm (eps = 0): rows scale by 1/sqrt(2.5) and 1/sqrt(4.625): maxima 2/sqrt(2.5), 3/sqrt(4.625)
+      LayerNorm (eps = 0): both rows become (1, -1): maxima 1, 1 -> (1/2 + 1/4) / 2 = 0.375"""
+    h = np.array([[1.0, -2.0], [3.0, 0.5]])[None, None]
+    v = np.array([[2.0, 1.0], [1.0, -4.0]])[None, None]
+    gb, ga = lo.transfer_gain(h, v, lo.RMS, 0.0)
+    assert gb.shape == (1, 1) and abs(gb[0, 0] - 0.875) < 1e-15
+    want = 0.5 * (2.0 / math.sqrt(2.5) / 2.0 + 3.0 / math.sqrt(4.625) / 4.0)      # 0.490604...
+    assert abs(want - 0.4906) < 1e-4 and abs(ga[0, 0] - want) < 1e-14
+    gb, ga = lo.transfer_gain(h, v, lo.LAYER, 0.0)
+    assert abs(gb[0, 0] - 0.875) < 1e-15 and abs(ga[0, 0] - 0.375) < 1e-14
+    # two (batch, head) slices are averaged separately
+    h2 = np.concatenate([h, 2.0 * h], axis=1)
+    v2 = np.concatenate([v, v], axis=1)
+    gb, _ = lo.transfer_gain(h2, v2, lo.RMS, 0.0)
+    assert gb.shape == (1, 2) and abs(gb[0, 1] - 1.75) < 1e-15
 
 
 @pytest.mark.parametrize("variant", [EXP, SIG])

@@ -273,3 +273,13 @@ def test_tile_width_override_changes_workspace_layout_not_validity(tfla):
     finally:
         assert lib.tfla_tile_width(0) == 0
     assert tfla.workspace_bytes(1, **a) == auto
+
+
+def test_error_type_carries_status_and_entry_point(tfla):
+    """every binding wrapper raises TflaError(status, entry point): the message names both"""
+    e = tfla.TflaError(-4, "tfla_transfer_gain")
+    assert e.status == -4 and "tfla_transfer_gain" in str(e) and "unknown variant" in str(e)
+    # no wrapper passes anything but (status, name) to the constructor
+    src = open(os.path.join(ROOT, "paper_2503_14376_amd", "binding.py")).read()
+    for m in re.finditer(r"raise TflaError\(([^)]*)\)", src):
+        assert len(m.group(1).split(",")) == 2, m.group(0)

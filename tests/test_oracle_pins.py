@@ -337,18 +337,38 @@ def test_p7_count_model_self_consistency():
     assert cm.flops_chunkwise_sig(T, 1, dqk, dhv) / cm.flops_recurrent_sig(T, dqk, dhv) < 1.01
 
 
+def _memop_table():
+    """rows[(row, column)] = list of (byte_type, c_dqk, c_dhv, c_dqkdhv, c_one) from the golden file."""
+    rows = {}
+    path = os.path.join(os.path.dirname(__file__), "golden", "recurrent_step_memory_operations.txt")
+    for line in open(path):
+        line = line.split("#")[0].split()
+        if len(line) == 7:
+            rows.setdefault((line[0], line[1]), []).append((line[2],) + tuple(int(x) for x in line[3:]))
+    return rows
+
+
+def _memop_eval(entries, dqk, dhv, nbytes):
+    return sum(nbytes[t] * (a * dqk + b * dhv + c * dqk * dhv + e) for t, a, b, c, e in entries)
+
+
 def test_p7_recurrent_step_memory_operations():
-    """App. F.2: totals of the recurrent formulation's memory-operation table.  Loads and stores of one
-    step add up to 2 bytes_if + 2 (d_hv + d_qk) bytes_qkv + 2 (d_hv d_qk + d_qk + 1) bytes_Cmn for
-    mLSTMexp and to the same without the n and m terms for mLSTMsig (the printed table swaps the two
-    totals between its columns: the load and store rows, which it is the sum of, decide)."""
+    """App. F.2, memory-operation table of the recurrent formulation: the count model equals the sum of the
+    table's load and store rows, typed entry by entry into tests/golden/ (not the same expression retyped).
+    The printed total row carries the two columns exchanged: it matches load + store of the other column."""
     from oracle import count_model as cm
-    for dqk, dhv in ((64, 64), (256, 512)):
-        for bq, bi, bc in ((2, 2, 4), (2, 4, 4), (4, 4, 4)):
-            exp_total = 2 * bi + 2 * (dhv + dqk) * bq + 2 * (dhv * dqk + dqk + 1) * bc
-            sig_total = 2 * bi + 2 * (dhv + dqk) * bq + 2 * dhv * dqk * bc
-            assert cm.bytes_recurrent_step_exp(dqk, dhv, bq, bi, bc) == exp_total
-            assert cm.bytes_recurrent_step_sig(dqk, dhv, bq, bi, bc) == sig_total
+    tab = _memop_table()
+    assert len(tab) == 6
+    fn = {"mLSTMexp": cm.bytes_recurrent_step_exp, "mLSTMsig": cm.bytes_recurrent_step_sig}
+    other = {"mLSTMexp": "mLSTMsig", "mLSTMsig": "mLSTMexp"}
+    for dqk, dhv in ((64, 64), (256, 512), (40, 24)):
+        for bq, bi, bc in ((2, 2, 4), (2, 4, 4), (4, 4, 4), (1, 3, 8)):
+            nb = {"qkv": bq, "if": bi, "Cmn": bc}
+            for col in fn:
+                rows_sum = _memop_eval(tab[("load", col)], dqk, dhv, nb) + _memop_eval(tab[("store", col)], dqk, dhv, nb)
+                assert fn[col](dqk, dhv, bq, bi, bc) == rows_sum
+                assert _memop_eval(tab[("total", other[col])], dqk, dhv, nb) == rows_sum
+                assert _memop_eval(tab[("total", col)], dqk, dhv, nb) != rows_sum
     # at the 7B head shape the matrix memory is > 99 % of the traffic: the step is bound by 2 d_qk d_hv floats
     tot = cm.bytes_recurrent_step_exp(256, 512)
     assert 2 * 256 * 512 * 4 / tot > 0.99

@@ -73,7 +73,7 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << 16).view(np.float32)
 
 
-def make_inputs(w: Workload, heads: Optional[int] = None) -> Dict[str, np.ndarray]:
+def make_inputs(w: Workload, heads: Optional[int] = None, slices=None) -> Dict[str, np.ndarray]:
     """Draw the input tensors of a workload (fp32 arrays; bf16 workloads are
     already rounded to bf16-representable values, so the oracle and the kernel
     both start from the same quantised inputs).
@@ -81,16 +81,23 @@ def make_inputs(w: Workload, heads: Optional[int] = None) -> Dict[str, np.ndarra
     heads: if given, only the first `heads` (batch*head) slices are drawn
     and returned with shape (1, heads, ...); slice s of the full problem is
     drawn from its own stream (seed, s), so the subset equals the full draw.
+    slices: instead of `heads`, an explicit list of (batch*head) slice indices
+    (b * NH + h), returned in that order with shape (1, len(slices), ...).
     """
     BH = w.B * w.NH
-    n = BH if heads is None else min(heads, BH)
-    shp = (w.B, w.NH) if heads is None else (1, n)
+    if slices is not None:
+        idx = [int(s) for s in slices]
+        assert heads is None and all(0 <= s < BH for s in idx)
+    else:
+        idx = list(range(BH if heads is None else min(heads, BH)))
+    n = len(idx)
+    shp = (w.B, w.NH) if (heads is None and slices is None) else (1, n)
 
     def draw(tag: int, tail, mean=0.0, std=1.0):
         out = np.empty((n,) + tuple(tail), dtype=np.float32)
-        for s in range(n):
+        for j, s in enumerate(idx):
             g = np.random.Generator(np.random.Philox(key=w.seed, counter=[tag, s, 0, 0]))
-            out[s] = g.standard_normal(tail, dtype=np.float32) * np.float32(std) + np.float32(mean)
+            out[j] = g.standard_normal(tail, dtype=np.float32) * np.float32(std) + np.float32(mean)
         return out.reshape(shp + tuple(tail))
 
     q = draw(1, (w.T, w.dqk))
@@ -148,3 +155,26 @@ def small(variant: int, dtype: int, B=1, NH=2, T=256, dqk=64, dhv=128, chunk=64,
     """A reduced workload of the same recipe for parity tests."""
     return Workload("small", B, NH, T, dqk, dhv, chunk, variant, dtype,
                     f_mean=f_mean, init_state=init_state, backward=backward, seed=seed)
+
+
+# ---- moving a drawn workload to the device / to the oracle's layout (no arithmetic) ----------------
+def to_dev(a, dtype):
+    """numpy array -> device tensor; bf16 workloads are bf16-representable already, so the cast is exact."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if dtype == BF16 else t
+
+
+def dev_inputs(w: Workload, d: Dict[str, np.ndarray]):
+    return {key: to_dev(val, w.dtype if key in ("q", "k", "v", "dH", "o_pre") else F32) for key, val in d.items()}
+
+
+def flat(a) -> np.ndarray:
+    """(B, NH, ...) -> (B*NH, ...) float64, the layout the oracle takes."""
+    a = np.asarray(a, dtype=np.float64)
+    return a.reshape((a.shape[0] * a.shape[1],) + a.shape[2:])
+
+
+def oracle_inputs(d: Dict[str, np.ndarray]):
+    keys = ("q", "k", "v", "i_pre", "f_pre", "C0", "n0", "m0")
+    return {k_: (flat(d[k_]) if k_ in d else None) for k_ in keys}
