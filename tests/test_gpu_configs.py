@@ -12,7 +12,15 @@ import workloads as wl
 from oracle import mlstm_oracle as orc
 
 pytestmark = pytest.mark.gpu
-NSAMPLE = 2   # (batch, head) slices checked against the oracle
+
+
+def _sample(w):
+    """(batch, head) slices checked against the oracle: the first, the last, and one from the middle of the
+    second batch element (or of the heads when there is one batch element) -- the slices a wrong grid decode,
+    slice stride or workspace offset would show in"""
+    BH = w.B * w.NH
+    mid = (w.NH + w.NH // 2 + 1) if w.B > 1 else w.NH // 2
+    return sorted({0, min(mid, BH - 1), BH - 1})
 
 
 def _run_fwd(w, dev):
@@ -21,14 +29,15 @@ def _run_fwd(w, dev):
                           dev.get("m0"), chunk=w.chunk, variant=w.variant, eps=1e-6)
 
 
-def _sub(t, n):
-    """first n (batch*head) slices of a (B, NH, ...) device tensor, as (1, n, ...)"""
-    return t.reshape((-1,) + tuple(t.shape[2:]))[:n].unsqueeze(0)
+def _sub(t, idx):
+    """the (batch*head) slices idx of a (B, NH, ...) device tensor, as (1, len(idx), ...)"""
+    sel = torch.as_tensor(idx, device=t.device, dtype=torch.long)
+    return t.reshape((-1,) + tuple(t.shape[2:])).index_select(0, sel).unsqueeze(0)
 
 
-def _check_fwd_sample(w, out, ref, n):
+def _check_fwd_sample(w, out, ref, idx):
     from tests import gpu_util as gu
-    sub = {k_: _sub(v_, n) for k_, v_ in out.items() if isinstance(v_, torch.Tensor) and v_.dim() >= 2 and k_ != "workspace"}
+    sub = {k_: _sub(v_, idx) for k_, v_ in out.items() if isinstance(v_, torch.Tensor) and v_.dim() >= 2 and k_ != "workspace"}
     errs = gu.check_fwd(w, None, sub, ref)
     print(w.name, "chunk", w.chunk, errs, flush=True)
     return errs
@@ -39,9 +48,10 @@ def test_config1_forward_with_initial_state():
     w = wl.CONFIGS["c1"]
     d = wl.make_inputs(w)
     out = _run_fwd(w, gu.dev_inputs(w, d))
-    ds = wl.make_inputs(w, heads=NSAMPLE)
+    idx = _sample(w)
+    ds = wl.make_inputs(w, slices=idx)
     ref = orc.recurrent_fwd(**gu.oracle_inputs(ds), variant=w.variant, eps=1e-6)
-    _check_fwd_sample(w, out, ref, NSAMPLE)
+    _check_fwd_sample(w, out, ref, idx)
 
 
 def test_config2_sig_chunk_sweep():
@@ -50,12 +60,13 @@ def test_config2_sig_chunk_sweep():
     w0 = wl.CONFIGS["c2"]
     d = wl.make_inputs(w0)
     dev = gu.dev_inputs(w0, d)
-    ds = wl.make_inputs(w0, heads=NSAMPLE)
+    idx = _sample(w0)
+    ds = wl.make_inputs(w0, slices=idx)
     ref = orc.recurrent_fwd(**gu.oracle_inputs(ds), variant=w0.variant, eps=1e-6)
     for L in wl.C2_CHUNKS:
         w = dataclasses.replace(w0, chunk=L)
         out = _run_fwd(w, dev)
-        _check_fwd_sample(w, out, ref, NSAMPLE)
+        _check_fwd_sample(w, out, ref, idx)
         for key in ("nn", "mn", "n_out", "m_out"):
             assert float(out[key].abs().max()) == 0.0     # no normaliser / max state in mLSTMsig
 
@@ -67,9 +78,10 @@ def test_config3_long_context_final_state_and_continuation():
     d = wl.make_inputs(w)
     dev = gu.dev_inputs(w, d)
     out = _run_fwd(w, dev)
-    ds = wl.make_inputs(w, heads=NSAMPLE)
+    idx = _sample(w)
+    ds = wl.make_inputs(w, slices=idx)
     ref = orc.recurrent_fwd(**gu.oracle_inputs(ds), variant=w.variant, eps=1e-6)
-    _check_fwd_sample(w, out, ref, NSAMPLE)
+    _check_fwd_sample(w, out, ref, idx)
     # chunked continuation: two calls over the halves, the state handed across, equal one call
     T1 = w.T // 2
     a = {k_: v_[:, :, :T1].contiguous() for k_, v_ in dev.items()}
@@ -95,13 +107,14 @@ def test_config4_forward_backward(name):
     bwd = tfla.mlstm_bwd(dev["q"], dev["k"], dev["v"], dev["i_pre"], dev["f_pre"], dev["dH"], fwd["n_out"], fwd["m_out"],
                          chunk=w.chunk, variant=w.variant, eps=1e-6, fwd_workspace=fwd["workspace"])
     torch.cuda.synchronize()
-    ds = wl.make_inputs(w, heads=NSAMPLE)
+    idx = _sample(w)
+    ds = wl.make_inputs(w, slices=idx)
     oi = gu.oracle_inputs(ds)
     ref_f = orc.recurrent_fwd(**oi, variant=w.variant, eps=1e-6)
-    _check_fwd_sample(w, fwd, ref_f, NSAMPLE)
+    _check_fwd_sample(w, fwd, ref_f, idx)
     ref = orc.chunkwise_bwd(**oi, dH=gu.flat(ds["dH"]), variant=w.variant, eps=1e-6, chunk=w.chunk)
     names = dict(dq="dq", dk="dk", dv="dv", d_i_pre="di", d_f_pre="df", dC0="dC0")
-    errs = {k_: gu.rel_err(_sub(bwd[k_], NSAMPLE), ref[r_]) for k_, r_ in names.items()}
+    errs = {k_: gu.rel_err(_sub(bwd[k_], idx), ref[r_]) for k_, r_ in names.items()}
     print(w.name, "backward", errs, flush=True)
     for k_, e in errs.items():
         assert e <= 2e-2, (k_, e, errs)
