@@ -72,8 +72,13 @@ enum {
     TFLA_ERR_CHUNK = -3,       /* not an allowed chunk size, or too many chunks              */
     TFLA_ERR_ENUM = -4,        /* unknown variant / dtype / direction                        */
     TFLA_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned (256 B) or too small            */
-    TFLA_ERR_STATE = -6        /* C0/n0/m0 (or Cn/nn/mn) only partly given                   */
+    TFLA_ERR_STATE = -6,       /* C0/n0/m0 (or Cn/nn/mn) only partly given                   */
+    TFLA_ERR_STATIC_LIMIT = -7 /* tfla_mlstm_fwd_static: the problem needs more scratch memory than
+                                  TFLA_STATIC_SCRATCH_BYTES                                      */
 };
+
+/* size of the scratch array behind tfla_mlstm_fwd_static: 64 MiB on every GPU the library is loaded on */
+#define TFLA_STATIC_SCRATCH_BYTES (64u << 20)
 
 /*
  * Forward pass (Sec. 2.2 / App. B.2 for the mathematics, Sec. 3 / App. C for the tiling).
@@ -96,6 +101,29 @@ TFLA_API int tfla_mlstm_fwd(const void* q, const void* k, const void* v,
                    void* H, float* Cn, float* nn, float* mn,
                    float* n_out, float* m_out,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The forward pass for callers that cannot allocate device memory or hand over a workspace: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels as tfla_mlstm_fwd without the workspace: the scratch memory is a file-scope device array of
+ * TFLA_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends; its address on
+ * the current device is looked up once, on the first call on that device, which therefore must not be under
+ * graph capture).  The call allocates and frees nothing and synchronises nothing.
+ *  - A problem whose tfla_mlstm_workspace_bytes(TFLA_FWD, ...) exceeds TFLA_STATIC_SCRATCH_BYTES is rejected
+ *    with TFLA_ERR_STATIC_LIMIT before anything is launched (tfla_static_scratch_bytes returns the limit).
+ *  - Every call on a GPU uses that GPU's one array: two calls whose kernels can overlap on one GPU (different
+ *    streams, or different threads) race on it; calls on one stream are ordered and safe.  The array keeps
+ *    the last call's contents; the kernels overwrite what they read, so nothing needs clearing in between.
+ *  - The array is not a forward workspace for tfla_mlstm_bwd: pass fwd_workspace = NULL there (recompute).
+ */
+TFLA_API int tfla_mlstm_fwd_static(const void* q, const void* k, const void* v,
+                   const float* i_pre, const float* f_pre,
+                   const float* C0, const float* n0, const float* m0,
+                   int B, int NH, int T, int dqk, int dhv,
+                   int chunk, int variant, int dtype, float eps,
+                   void* H, float* Cn, float* nn, float* mn,
+                   float* n_out, float* m_out, void* stream);
+TFLA_API size_t tfla_static_scratch_bytes(void);
 
 /*
  * Backward pass (App. B.3, App. C.4).  Computes the gradient of

@@ -17,7 +17,8 @@ _lib = None
 EXPORTS = ("tfla_mlstm_fwd", "tfla_mlstm_bwd", "tfla_mlstm_step", "tfla_mlstm_workspace_bytes", "tfla_mlstm_check",
            "tfla_status_string", "tfla_version", "tfla_profile_enable", "tfla_profile_read",
            "tfla_profile_kernels", "tfla_mlstm_layer_fwd", "tfla_mlstm_layer_bwd", "tfla_mlstm_layer_workspace_bytes",
-           "tfla_transfer_gain", "tfla_mlstm_layer_step", "tfla_tile_width")
+           "tfla_transfer_gain", "tfla_mlstm_layer_step", "tfla_tile_width", "tfla_mlstm_fwd_static",
+           "tfla_static_scratch_bytes")
 
 
 class TflaError(RuntimeError):
@@ -43,6 +44,11 @@ def load_library():
     lib.tfla_mlstm_fwd.restype = ci
     lib.tfla_mlstm_fwd.argtypes = [vp, vp, vp, fp, fp, fp, fp, fp, ci, ci, ci, ci, ci, ci, ci, ci, cf,
                                    vp, fp, fp, fp, fp, fp, vp, sz, vp]
+    lib.tfla_mlstm_fwd_static.restype = ci
+    lib.tfla_mlstm_fwd_static.argtypes = [vp, vp, vp, fp, fp, fp, fp, fp, ci, ci, ci, ci, ci, ci, ci, ci, cf,
+                                          vp, fp, fp, fp, fp, fp, vp]
+    lib.tfla_static_scratch_bytes.restype = sz
+    lib.tfla_static_scratch_bytes.argtypes = []
     lib.tfla_mlstm_bwd.restype = ci
     lib.tfla_mlstm_bwd.argtypes = [vp, vp, vp, fp, fp, fp, fp, fp, fp, fp, vp, fp, ci, ci, ci, ci, ci, ci, ci, ci, cf,
                                    vp, vp, vp, fp, fp, fp, vp, sz, vp, sz, vp]
@@ -180,6 +186,39 @@ def mlstm_fwd(q, k, v, i_pre, f_pre, C0=None, n0=None, m0=None, chunk=256, varia
     if rc != 0:
         raise TflaError(rc, "tfla_mlstm_fwd")
     o["workspace"] = workspace
+    return o
+
+
+def static_scratch_bytes() -> int:
+    return int(load_library().tfla_static_scratch_bytes())
+
+
+def mlstm_fwd_static(q, k, v, i_pre, f_pre, C0=None, n0=None, m0=None, chunk=256, variant=EXP, eps=1e-6, stream=None,
+                     out: Optional[Dict] = None) -> Dict:
+    """tfla_mlstm_fwd_static on torch device tensors: the forward pass on the library's own static scratch memory.
+    `out` must hold every output tensor (H, Cn, nn, mn, n_out, m_out; the state and per-step entries may be
+    missing = not wanted): this wrapper allocates nothing either."""
+    import torch
+    lib = load_library()
+    B, NH, T, dqk = q.shape
+    dhv = v.shape[-1]
+    dtype = BF16 if q.dtype == torch.bfloat16 else F32
+    td, f32 = _torch_dtype(dtype), torch.float32
+    _want(q, td, (B, NH, T, dqk), "q"); _want(k, td, (B, NH, T, dqk), "k"); _want(v, td, (B, NH, T, dhv), "v")
+    _want(i_pre, f32, (B, NH, T), "i_pre"); _want(f_pre, f32, (B, NH, T), "f_pre")
+    _want(C0, f32, (B, NH, dqk, dhv), "C0"); _want(n0, f32, (B, NH, dqk), "n0"); _want(m0, f32, (B, NH), "m0")
+    if out is None or "H" not in out:
+        raise ValueError("mlstm_fwd_static writes into caller-provided tensors: pass out={'H': ..., ...}")
+    o = out
+    _want(o["H"], td, (B, NH, T, dhv), "H"); _want(o.get("Cn"), f32, (B, NH, dqk, dhv), "Cn")
+    _want(o.get("nn"), f32, (B, NH, dqk), "nn"); _want(o.get("mn"), f32, (B, NH), "mn")
+    _want(o.get("n_out"), f32, (B, NH, T), "n_out"); _want(o.get("m_out"), f32, (B, NH, T), "m_out")
+    rc = lib.tfla_mlstm_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(i_pre), _ptr(f_pre), _ptr(C0), _ptr(n0), _ptr(m0),
+                                   B, NH, T, dqk, dhv, int(chunk), int(variant), dtype, float(eps),
+                                   _ptr(o["H"]), _ptr(o.get("Cn")), _ptr(o.get("nn")), _ptr(o.get("mn")),
+                                   _ptr(o.get("n_out")), _ptr(o.get("m_out")), _stream_handle(stream))
+    if rc != 0:
+        raise TflaError(rc, "tfla_mlstm_fwd_static")
     return o
 
 

@@ -5,6 +5,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 using namespace tfla;
 
 namespace tfla { int tile_width_override = 0; }
@@ -540,6 +542,40 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
 
 }  // namespace
 
+// ---- scratch memory of the allocation-free forward entry point -------------------------------------
+// One array per GPU the library runs on, part of the code object: it exists from the moment the module is
+// loaded on a device until the process ends.  In host code its name is only the handle that
+// hipGetSymbolAddress translates; kernels and copies get the translated address.
+namespace tfla {
+static __device__ __align__(256) unsigned char scratch[TFLA_STATIC_SCRATCH_BYTES];
+// never launched: a device-side use of the array, so that it is kept in the code object
+__global__ void static_scratch_probe_kernel(unsigned* out) { *out = scratch[0]; }
+}  // namespace tfla
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};      // device address of `scratch` on each device, set on first use
+
+// address of the current device's copy of the array; nothing here allocates
+int static_scratch_address(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= MAX_DEVICES) return TFLA_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(tfla::scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return TFLA_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int tfla_version(void) { return 1200; }
@@ -594,6 +630,7 @@ const char* tfla_status_string(int status) {
         case TFLA_ERR_ENUM: return "unknown variant, dtype or direction";
         case TFLA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
         case TFLA_ERR_STATE: return "state must be given completely (C, n, m) or not at all; n_out/m_out must not alias n/m";
+        case TFLA_ERR_STATIC_LIMIT: return "the problem needs more scratch memory than the static buffer of the allocation-free entry point holds (tfla_static_scratch_bytes)";
         default: break;
     }
     if (status > 0) return hipGetErrorString((hipError_t)status);
@@ -618,6 +655,28 @@ int tfla_mlstm_fwd(const void* q, const void* k, const void* v, const float* i_p
                    float* n_out, float* m_out, void* workspace, size_t workspace_bytes, void* stream) {
     return fwd_impl(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, dqk, dhv, chunk, variant, dtype, eps, 0.0f, H, Cn, nn,
                     mn, n_out, m_out, workspace, workspace_bytes, stream);
+}
+
+size_t tfla_static_scratch_bytes(void) { return (size_t)TFLA_STATIC_SCRATCH_BYTES; }
+
+int tfla_mlstm_fwd_static(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,
+                          const float* C0, const float* n0, const float* m0, int B, int NH, int T, int dqk, int dhv,
+                          int chunk, int variant, int dtype, float eps, void* H, float* Cn, float* nn, float* mn,
+                          float* n_out, float* m_out, void* stream) {
+    // everything that can be rejected is rejected before the first HIP call
+    const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (rc != TFLA_OK) return rc;
+    const size_t need = tfla_mlstm_workspace_bytes(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
+    if (need == 0) return TFLA_ERR_SHAPE;
+    if (need > (size_t)TFLA_STATIC_SCRATCH_BYTES) return TFLA_ERR_STATIC_LIMIT;
+    if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
+    void* ws = nullptr;
+    const int st = static_scratch_address(&ws);
+    if (st != TFLA_OK) return st;
+    // the kernels write every part of the scratch memory they later read (gate vectors, chunk states), so
+    // nothing has to be cleared between calls; the previous call's contents are simply overwritten
+    return fwd_impl(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, dqk, dhv, chunk, variant, dtype, eps, 0.0f, H, Cn, nn,
+                    mn, n_out, m_out, ws, (size_t)TFLA_STATIC_SCRATCH_BYTES, stream);
 }
 
 int tfla_mlstm_bwd(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre,

@@ -283,3 +283,23 @@ def test_error_type_carries_status_and_entry_point(tfla):
     src = open(os.path.join(ROOT, "paper_2503_14376_amd", "binding.py")).read()
     for m in re.finditer(r"raise TflaError\(([^)]*)\)", src):
         assert len(m.group(1).split(",")) == 2, m.group(0)
+
+
+def test_static_entry_point_rejects_before_touching_the_gpu(tfla):
+    """tfla_mlstm_fwd_static validates dimensions, the size limit and the pointers before its first HIP call,
+    so these codes come back on a machine without a GPU as well"""
+    lib = tfla.load_library()
+    P = lambda x: ctypes.c_void_p(x * 4096) if x else None
+    cf = ctypes.c_float
+    assert tfla.static_scratch_bytes() == 64 << 20
+
+    def call(B=1, NH=2, T=256, dqk=64, dhv=128, chunk=64, q=1, H=1, variant=0, dtype=1):
+        return lib.tfla_mlstm_fwd_static(P(q), P(1), P(1), P(1), P(1), None, None, None, B, NH, T, dqk, dhv, chunk,
+                                         variant, dtype, cf(1e-6), P(H), None, None, None, None, None, None)
+    assert call(B=2, NH=8, T=8192, dqk=256, dhv=512, chunk=256) == -7      # needs ~140 MB of scratch memory
+    assert "static" in tfla.status_string(-7)
+    assert call(chunk=48) == -3
+    assert call(dqk=0) == -2
+    assert call(variant=5) == -4
+    assert call(q=0) == -1
+    assert call(H=0) == -1
