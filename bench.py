@@ -178,6 +178,7 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--variant", default="")
     ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--seq-len", type=int, default=0, help="override T of the workload (a secondary line)")
     ap.add_argument("--head-dim", type=int, default=0,
                     help="head-dimension sweep point of App. E.3: dqk = dhv = this value, NH = 4096 / value, B = 4 "
                          "(unless --batch), T = 8192; a secondary line")
@@ -225,6 +226,8 @@ def main() -> int:
                                 NH=4096 // args.head_dim, B=4, T=8192)
     if args.batch:
         w = dataclasses.replace(w, B=args.batch)
+    if args.seq_len:
+        w = dataclasses.replace(w, T=args.seq_len)
     do_bwd = not args.fwd_only
     if do_bwd and not w.backward:
         w = dataclasses.replace(w, backward=True)

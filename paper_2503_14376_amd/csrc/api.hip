@@ -15,9 +15,6 @@ namespace {
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// chunks between the anchors of the forget-gate gradient scan (see bwd_core)
-constexpr int ANCHOR_CHUNKS = 4;
-
 struct Dims {
     int B, NH, T, dqk, dhv, L, variant, dtype;   // T: whole chunks (the padded length when the caller's is ragged)
     long BH, BHT;
@@ -78,8 +75,12 @@ struct Carver {
 // The forward workspace doubles as the record the backward call can reuse (gate vectors, the
 // chunk states C_{k-1} and the final state), so its layout is part of the library's contract
 // with itself: carve_fwd is the only place that defines it.
+// boundaries between the blocks of the anchored forget-gate gradient scan, plus the unused slot 0
+inline int anchor_G(const Dims& d) { return anchor_chunks(d.L, d.dqk > d.dhv ? d.dqk : d.dhv); }
+inline size_t anchor_slots(const Dims& d) { const int G = anchor_G(d); return (size_t)((d.Nc + G - 1) / G); }
+
 struct FwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *nst, *Cfin, *pacc, *pnrm;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *nst, *Cfin, *pacc, *pnrm, *anc;
     void* stT;
     size_t bytes;
 };
@@ -96,12 +97,14 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
     // d_qk above 512: the parallel kernel contracts over d_qk in two halves that meet in fp32
     w.pacc = d.dqk > 512 ? c.take<float>((size_t)d.BHT * d.dhv) : nullptr;
     w.pnrm = d.dqk > 512 ? c.take<float>(d.BHT) : nullptr;
+    // bf16: fp32 copies of the state at the block boundaries of the forget-gate gradient scan (see bwd_core)
+    w.anc = d.dtype == TFLA_BF16 ? c.take<float>(anchor_slots(d) * (size_t)d.BH * d.dqk * d.dhv) : nullptr;
     w.bytes = c.off;
     return w;
 }
 
 struct BwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal, *anchor, *pacc;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal, *anchor, *pacc, *ancC;
     double* bsum;
     void *cN, *dcT, *dcN, *E, *E2;
     int nbQ, nbK;
@@ -120,7 +123,6 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.nbK = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DK, d.L);
     w.partQ = c.take<float>((size_t)w.nbQ * d.BHT); w.partK = c.take<float>((size_t)w.nbK * d.BHT);
     w.cdot = c.take<float>(d.BH);
-    w.anchor = c.take<float>(d.BH * d.Nc);
     w.Cfinal = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
     const size_t st = (size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz;
     // bf16: C_{k-1} and dC_k, both as (d_hv, d_qk); fp32 additionally dC_k as (d_qk, d_hv)
@@ -133,6 +135,10 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     const int dwide = d.dqk > d.dhv ? d.dqk : d.dhv;
     w.pacc = dwide > 512 ? c.take<float>((size_t)d.BHT * dwide) : nullptr;
     w.E2 = (d.dtype == TFLA_BF16 && d.dhv > 512) ? c.take_bytes((size_t)d.BHT * d.L * d.esz) : nullptr;
+    // bf16: fp32 boundary copies of C (used when the states are recomputed here), and the partial inner products
+    // <C, dC> of every boundary
+    w.ancC = d.dtype == TFLA_BF16 ? c.take<float>(anchor_slots(d) * (size_t)d.BH * d.dqk * d.dhv) : nullptr;
+    w.anchor = c.take<float>(anchor_slots(d) * (size_t)d.BH * rec_anchor_parts(d.dqk, d.dhv));
     w.bytes = c.off;
     return w;
 }
@@ -235,6 +241,7 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     r.stT = w.stT; r.stN = nullptr; r.Sfinal = Cn; r.Sfinal2 = w.Cfin;
     r.n0 = is_exp ? n0 : nullptr; r.nst = is_exp ? w.nst : nullptr; r.nfinal = is_exp ? nn : nullptr;
     r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
+    r.anc = w.anc; r.anc_in = nullptr; r.anc_part = nullptr; r.anc_G = anchor_G(d);
     TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
 
     // 3. parallel kernel
@@ -320,6 +327,7 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
         r.Sfinal = dCn ? w.Cfinal : nullptr; r.Sfinal2 = nullptr;
         r.n0 = nullptr; r.nst = nullptr; r.nfinal = nullptr;
         r.T = T; r.L = chunk; r.Nc = d.Nc; r.d1 = dqk; r.d2 = dhv; r.reverse = 0;
+        r.anc = w.ancC; r.anc_in = nullptr; r.anc_part = nullptr; r.anc_G = anchor_G(d);
         TFLA_LAUNCH(K_REC_FWD, launch_recurrent(r, (int)d.BH, dtype, s));
     }
 
@@ -329,6 +337,10 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     rb.stT = w.dcT; rb.stN = tonly ? nullptr : w.dcN; rb.Sfinal = dC0; rb.Sfinal2 = nullptr;
     rb.n0 = nullptr; rb.nst = nullptr; rb.nfinal = nullptr;
     rb.T = T; rb.L = chunk; rb.Nc = d.Nc; rb.d1 = dqk; rb.d2 = dhv; rb.reverse = 1;
+    // bf16: the reversed launch also forms <C, dC> at the block boundaries of the forget-gate gradient scan, from the
+    // fp32 copies of C that the forward launch left there and its own fp32 accumulators
+    rb.anc = nullptr; rb.anc_in = tonly ? (reuse_states ? fw.anc : w.ancC) : nullptr; rb.anc_part = tonly ? w.anchor : nullptr;
+    rb.anc_G = anchor_G(d);
     TFLA_LAUNCH(K_REC_BWD, launch_recurrent(rb, (int)d.BH, dtype, s));
 
     // 4. the three gradient kernels
@@ -354,16 +366,15 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     gg.partQ = w.partQ; gg.nbQ = w.nbQ; gg.partK = w.partK; gg.nbK = w.nbK; gg.cdot = dCn ? w.cdot : nullptr;
     gg.i_pre = i_pre; gg.f_pre = f_pre; gg.d_i = d_i_pre; gg.d_f = d_f_pre; gg.T = T; gg.variant = variant;
     gg.BHT = d.BHT; gg.bsum = w.bsum; gg.softcap = softcap;
-    gg.anchor = nullptr; gg.L = chunk; gg.Nc = d.Nc; gg.G = 1;
-    // bf16: the forget-gate scan is anchored with <C_k, dC_k> at the end of every block of ANCHOR_CHUNKS chunks
-    // (fewer when the chunks are long: a block has at most 2048 steps), so that the rounding noise of its terms
-    // (one part in 2^9 of the boundary terms per chunk, from the bf16 states) accumulates over one block
-    // instead of the whole sequence; the cost is one read of both states at every block boundary.
+    gg.anchor = nullptr; gg.L = chunk; gg.Nc = d.Nc; gg.G = 1; gg.npart = 0;
+    // bf16: the forget-gate scan is anchored with <C_k, dC_k> at the end of every block of anchor_chunks() chunks
+    // (a block has at most 2048 steps), so that the rounding noise of its terms (one part in 2^9 of the boundary
+    // terms per chunk, from the bf16 states) accumulates over one block instead of the whole sequence.  The anchors
+    // themselves are exact to fp32: the forward recurrent launch leaves fp32 copies of the state at the block
+    // boundaries and the reversed launch multiplies them with its fp32 accumulators (see RecArgs).
     if (tonly) {
-        gg.G = ANCHOR_CHUNKS * chunk <= 2048 ? ANCHOR_CHUNKS : (2048 / chunk > 0 ? 2048 / chunk : 1);
-        TFLA_LAUNCH(K_STATE_DOT, launch_chunk_anchors(cstates, w.dcT, dCn ? w.cdot : nullptr, w.anchor, d.Nc, gg.G,
-                                                      (long)dqk * dhv, (int)d.BH, s));
-        gg.anchor = w.anchor;
+        gg.G = anchor_G(d);
+        gg.anchor = w.anchor; gg.npart = rec_anchor_parts(dqk, dhv);
     }
     TFLA_LAUNCH(K_GATE_GRADS, launch_gate_grads(gg, (int)d.BH, s));
     return TFLA_OK;

@@ -345,9 +345,23 @@ __global__ void __launch_bounds__(256) gate_grads_anchored_kernel(GateGradArgs a
     if (lane == 0) wt[wave] = x;
     __syncthreads();
     for (int w = wave + 1; w < 4; ++w) excl += wt[w];
-    // the anchor at the end of the block arrives in one partial sum per chunk of the block
+    // the anchor at the end of the block: <C_T, dC_T> (or nothing) at the end of the sequence, else <C, dC> at the
+    // boundary after the block, which the reversed recurrent launch left as npart partial sums
+    __shared__ double wa[4];
     double anc = 0.0;
-    for (int s_ = kc0; s_ < kc1; ++s_) anc += (double)a.anchor[(long)bh * a.Nc + s_];
+    if (kc1 == a.Nc) {
+        anc = a.cdot ? (double)a.cdot[bh] : 0.0;
+    } else {
+        const int nslot = (a.Nc + a.G - 1) / a.G;
+        const float* pp = a.anchor + ((long)bh * nslot + kc1 / a.G) * a.npart;
+        double ps = 0.0;
+        for (int q = tid; q < a.npart; q += 256) ps += (double)pp[q];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ps += __shfl_xor(ps, o, 64);
+        if (lane == 0) wa[wave] = ps;
+        __syncthreads();
+        anc = (wa[0] + wa[1]) + (wa[2] + wa[3]);
+    }
     double run = excl + anc;
 #pragma unroll
     for (int e = 7; e >= 0; --e) {
@@ -359,46 +373,6 @@ __global__ void __launch_bounds__(256) gate_grads_anchored_kernel(GateGradArgs a
             a.d_i[row + t] = (a.variant == 0 ? c[e] : c[e] * sigmoid_neg(soft_cap(ip, a.softcap))) * soft_cap_grad(ip, a.softcap);
         }
     }
-}
-
-// Anchor of every block of G chunks: <C, dC> at the block's end (cdot at the end of the sequence).  The product
-// over the `per` state elements is split between as many workgroups as the block has chunks; workgroup s
-// leaves its partial sum in the anchor slot of the block's chunk s, and the scan adds the slots of its block.
-__global__ void __launch_bounds__(256) chunk_anchors_kernel(const bf16_t* Cst, const bf16_t* dCst, const float* cdot,
-                                                            float* anchor, int Nc, int G, long per) {
-    __shared__ double wt[4];
-    const int kc0 = (int)blockIdx.x * G, kc1 = min(kc0 + G, Nc), nsl = kc1 - kc0, sl = blockIdx.z;
-    const int bh = blockIdx.y, tid = threadIdx.x;
-    if (sl >= nsl) return;
-    const int kc = kc1 - 1;                          // the block ends after chunk kc
-    float* out = anchor + (long)bh * Nc + kc0 + sl;
-    if (kc == Nc - 1) {
-        if (tid == 0) *out = (sl == 0 && cdot) ? cdot[bh] : 0.0f;
-        return;
-    }
-    const bf16_t* A = Cst + ((long)bh * Nc + kc + 1) * per;
-    const bf16_t* B = dCst + ((long)bh * Nc + kc) * per;
-    const long lo = (per / 8 * sl / nsl) * 8, hi = (per / 8 * (sl + 1) / nsl) * 8;     // 16-byte aligned slices
-    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (long i = lo + (long)tid * 8; i < hi; i += 256 * 8) {
-        const u32x4 x = *reinterpret_cast<const u32x4*>(A + i), y = *reinterpret_cast<const u32x4*>(B + i);
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            acc[e] += bf16_lo_to_f32(x[e]) * bf16_lo_to_f32(y[e]) + bf16_hi_to_f32(x[e]) * bf16_hi_to_f32(y[e]);
-    }
-    double tot = ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o, 64);
-    if ((tid & 63) == 0) wt[tid >> 6] = tot;
-    __syncthreads();
-    if (tid == 0) *out = (float)((wt[0] + wt[1]) + (wt[2] + wt[3]));
-}
-hipError_t launch_chunk_anchors(const void* Cst, const void* dCst, const float* cdot, float* anchor, int Nc, int G, long per,
-                                int BH, hipStream_t s) {
-    if (G < 1 || G > 64 || per % 8 != 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(chunk_anchors_kernel, dim3((Nc + G - 1) / G, BH, G), dim3(256), 0, s, reinterpret_cast<const bf16_t*>(Cst),
-                       reinterpret_cast<const bf16_t*>(dCst), cdot, anchor, Nc, G, per);
-    return hipGetLastError();
 }
 
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s) {

@@ -248,7 +248,10 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
             for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[mi][v]));
         TFragReader<BM> ra; ra.init(lane, 8);
         TFragReader<BN> rb; rb.init(lane, 8);
-        const uint32_t boff = rb.block_offset(wc);  // LDS byte offset of this wave's B column block
+        uint32_t boff = rb.block_offset(wc);        // LDS byte offset of this wave's B column block
+        // (the compiler may fetch this from a small table in memory: make it wait for that here, because a wait
+        // that it places inside the loop would also wait for every global->LDS load in flight)
+        asm volatile("" : "+v"(boff));
         // the consumers fetch the Y pieces (same order and address stepping as the producers' X)
         DY dy; dy.init(a.d2, tid);
         const long row0 = a.reverse ? (long)(a.Nc - 1) * a.L : 0;
@@ -319,6 +322,49 @@ __global__ void __launch_bounds__(WN * 128) recurrent_kernel_bf16(RecArgs a) {
                             const int n = q * 8 + (lane >> 3), c = lane & 7;
                             const u32x4 w = *reinterpret_cast<const u32x4*>(ot + n * 128 + ((c ^ (n & 7)) * 16));
                             *reinterpret_cast<u32x4*>(gdst + ((long)(16 * h + n) * a.d1 + 8 * c) * 2) = w;
+                        }
+                        asm volatile("" ::: "memory");
+                    }
+                }
+                // Boundaries between the blocks of the forget-gate gradient scan (the state here is the one between
+                // chunks kb - 1 and kb): the forward launch leaves an fp32 copy of its accumulators, the reversed
+                // launch multiplies that copy with its own and leaves the partial inner product.
+                if (a.anc || a.anc_in) {
+                    const int kb = a.reverse ? kc + 1 : kc;
+                    if (kb % a.anc_G == 0 && kb > 0 && kb < a.Nc) {
+                        const long per = (long)a.d1 * a.d2;
+                        const int nslot = (a.Nc + a.anc_G - 1) / a.anc_G;
+                        const int part = (by * (int)gridDim.x + bx) * WN + wc;
+                        const long off = ((long)bh * nslot + kb / a.anc_G) * per + ((long)part * (MI * 4) * 64 + lane) * 4;
+                        if (a.anc) {
+                            st0 += MI * 4;
+#pragma unroll
+                            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    const f32x4 w = {acc[mi][4 * j], acc[mi][4 * j + 1], acc[mi][4 * j + 2], acc[mi][4 * j + 3]};
+                                    *reinterpret_cast<f32x4*>(a.anc + off + (long)(mi * 4 + j) * 256) = w;
+                                }
+                        }
+                        if (a.anc_in) {
+                            f32x4 c[MI * 4];
+#pragma unroll
+                            for (int q = 0; q < MI * 4; ++q) c[q] = *reinterpret_cast<const f32x4*>(a.anc_in + off + (long)q * 256);
+                            float dot = 0.0f;
+#pragma unroll
+                            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) dot += acc[mi][4 * j + e] * c[mi * 4 + j][e];
+                            // Everything this wavefront has in flight has landed once these plain loads have (the
+                            // compiler's own wait for them may or may not say so; this one does).  Operations from
+                            // before this point can then never be younger than a piece that is still awaited, so the
+                            // wait counts below stay valid without knowing about the loads.
+                            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                            dot = wave_sum(dot);
+                            if (lane == 0) a.anc_part[((long)bh * nslot + kb / a.anc_G) * (gridDim.x * gridDim.y * WN) + part] = dot;
+                            st0 += 1;
                         }
                         asm volatile("" ::: "memory");
                     }

@@ -45,9 +45,9 @@ struct GateGradArgs {
     int T, variant; long BHT;
     float softcap;                 // as in GateArgs: the gradients are taken through the cap
     // optional anchors of the reverse cumulative sum, one per block of G chunks (G * L <= 2048): its exact value
-    // just after the last step of the block, as the sum of the anchor slots of the block's chunks (see
-    // launch_chunk_anchors); NULL = one scan over the whole sequence
-    const float* anchor; int L, Nc, G;
+    // just after the last step of the block, <C, dC> at that boundary, as npart partial sums per boundary
+    // (RecArgs::anc_part: (BH, nslot, npart)); NULL = one scan over the whole sequence
+    const float* anchor; int L, Nc, G, npart;
 };
 hipError_t launch_gate_grads(const GateGradArgs& a, int BH, hipStream_t s);
 
@@ -61,12 +61,13 @@ hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, 
 hipError_t launch_pad_scalar(const float* in, float* out, long BH, int T, int Tp, float fill, hipStream_t s);
 hipError_t launch_unpad_scalar(const float* in, float* out, long BH, int T, int Tp, hipStream_t s);
 hipError_t launch_state_dot(const float* A, const float* Bm, float* out, long per, int BH, hipStream_t s);
-// For every block of G chunks ending after chunk k: <C_{k+1}, dC_{k+1}> (bf16 chunk states as the recurrent
-// kernel stores them: Cst[bh][k] is the state before chunk k, dCst[bh][k] the gradient of the state after
-// chunk k), or cdot[bh] (or 0) at the end of the sequence, left as partial sums in the anchor slots
-// anchor[bh][first chunk of the block ...] (one per chunk of the block)
-hipError_t launch_chunk_anchors(const void* Cst, const void* dCst, const float* cdot, float* anchor, int Nc, int G, long per,
-                                int BH, hipStream_t s);
+// Chunks per block of the anchored forget-gate gradient scan: four (a block has at most 2048 steps); one for heads
+// wider than 512, where a row's dot products run over so many terms that the noise of a few chunks already shows
+// (behind a norm layer the forget-gate gradient is what survives of an almost complete cancellation).
+inline int anchor_chunks(int L, int dwide) {
+    if (dwide > 512) return 1;
+    return 4 * L <= 2048 ? 4 : (2048 / L > 0 ? 2048 / L : 1);
+}
 
 // ---- single recurrent step (Sec. 2.1, Sec. 4.1) ------------------------------------------------
 struct StepArgs {
@@ -135,8 +136,18 @@ struct RecArgs {
                           // bytes as (BH, Nc, 2, d1) bf16: n rounded to bf16, and the rounding remainder
     float* nfinal;        // (BH, d1) or NULL
     int T, L, Nc, d1, d2, reverse;
+    // bf16 kernel only, for the anchors of the forget-gate gradient scan (the boundaries between its blocks of anc_G
+    // chunks; slot s = the boundary between chunks s * anc_G - 1 and s * anc_G, slot 0 unused):
+    //   anc      (forward launch) receives fp32 copies of the state at those boundaries, (BH, nslot, d1 * d2) in the
+    //            order of the kernel's accumulator registers;
+    //   anc_in   (reversed launch) = what the forward launch left in anc: every wavefront multiplies its part of it
+    //            with its fp32 accumulators (the same element order) and leaves the partial inner product in
+    //   anc_part (BH, nslot, npart), npart = (d1 / 64) * (d2 / 32) = rec_anchor_parts().
+    // NULL = none.
+    float* anc; const float* anc_in; float* anc_part; int anc_G;
 };
 hipError_t launch_recurrent(const RecArgs& a, int BH, int dtype, hipStream_t s);
+inline int rec_anchor_parts(int d1, int d2) { return (d1 / 64) * (d2 / 32); }
 
 // ---- intra-chunk tiled kernels (Sec. 3, App. C.3 Alg. 1, App. C.4) ---------------------------
 // out[r,:] = sum_c exp2(wrow[r] + wcol[c]) * (X_r . Y_c) * Z_c  (causal within the chunk)
@@ -148,6 +159,7 @@ struct TileArgs {
     const float* wrow; const float* wcol; const float* srow;   // (BH, T)
     const void* St;                 // (BH, Nc, d2, d1)
     int T, L, Nc, d1, d2;
+    int kc_desc;                    // bf16 kernels: walk the chunks last to first (set by the launcher)
     // MODE_H, mLSTMexp: normaliser
     int variant; float eps;
     const float* nstate;            // (BH, Nc, d1); bf16 kernels: (BH, Nc, 2, d1) bf16 as RecArgs::nst
@@ -168,6 +180,10 @@ struct TileArgs {
     float* acc_out; float* nrm_out;             // store the raw accumulators / normaliser instead of the output
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
+// bf16 H and dV (mode MODE_H / MODE_DV) with one workgroup per 256 rows that walks all column blocks (tile_walk.h):
+// contraction widths 128 and 256, output widths that are multiples of 128, chunks that are multiples of 256
+inline bool tile_walk_supported(int d1, int d2, int L) { return (d1 == 128 || d1 == 256) && d2 % 128 == 0 && L % 256 == 0; }
+hipError_t launch_tile_walk(const TileArgs& a, int mode, int BH, hipStream_t s);
 // d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16
 // wavefront within 256 registers, so that two workgroups share a CU when d1 <= 256.  The bf16 dQ and
 // dK kernels take a 256-wide block when d1 = 512 (one workgroup per CU anyway): half as many

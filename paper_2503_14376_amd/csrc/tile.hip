@@ -304,7 +304,21 @@ template <int MODE>
 hipError_t launch_tile_mode(const TileArgs& a0, int BH, int dtype, hipStream_t s) {
     TileArgs a = a0;
     a.acc_in = nullptr; a.nrm_in = nullptr; a.acc_out = nullptr; a.nrm_out = nullptr;
+    // Chunk order of each kernel of the sequence gates -> recurrence (first to last) -> H and
+    // reversed recurrence (last to first) -> dV -> dQ -> dK: each starts at the end of the sequence where its
+    // predecessor stopped.
+#ifndef TFLA_KC_ORDER
+#define TFLA_KC_ORDER 0x5   // bit m = direction of mode m: H descending, dV ascending, dQ descending, dK ascending
+#endif
+    a.kc_desc = ((TFLA_KC_ORDER) >> MODE) & 1;
     const int bd2 = tile_bd2(a.d1, a.d2, dtype, MODE, a.L);
+    // H and dV at contraction widths 128 / 256 with chunks that are multiples of 256: one workgroup per 256 rows
+    // walks all column blocks (tile_walk.h)
+#ifdef TFLA_USE_WALK
+    if constexpr (MODE == MODE_H || MODE == MODE_DV) {
+        if (dtype == 1 && tile_width_override == 0 && tile_walk_supported(a.d1, a.d2, a.L)) return launch_tile_walk(a, MODE, BH, s);
+    }
+#endif
     if (dtype != 1) return a.d1 > 256 ? hipErrorInvalidValue : launch_tile_m<float, MODE>(a, BH, bd2, s);
     if (a.d1 <= 512) return launch_tile_m<bf16_t, MODE>(a, BH, bd2, s);
     // d1 = 1024: the kernels hold a workgroup's X rows in registers, which ends at 512 columns.  Every term of

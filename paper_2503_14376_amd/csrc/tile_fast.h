@@ -79,8 +79,16 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     const int nb2 = __builtin_amdgcn_readfirstlane((int)(wg % gx)); wg /= gx;
     const int rbi = __builtin_amdgcn_readfirstlane((int)(wg % gy)); wg /= gy;
     const int rb = UPPER ? rbi : (int)gy - 1 - rbi;      // row blocks with more column tiles first
-    const int kc = __builtin_amdgcn_readfirstlane((int)(wg % a.Nc));
-    const int bh = __builtin_amdgcn_readfirstlane((int)(wg / a.Nc));
+    // Order in time: every XCD walks the chunks of its own (batch, head) slices together, chunk by chunk, in
+    // the direction a.kc_desc gives -- the launcher picks the direction that starts where the kernel before
+    // this one stopped, so that what that kernel read or wrote last is still in the memory-side cache.
+    // bpx = slices per XCD (the XCD's contiguous range of ids then covers exactly its slices)
+    const unsigned bhn = nwg / (gx * gy * (unsigned)a.Nc);
+    const unsigned bpx = (bhn % 8u == 0u) ? bhn / 8u : 1u;
+    const unsigned bl = wg % bpx; wg /= bpx;
+    const int kci = __builtin_amdgcn_readfirstlane((int)(wg % a.Nc));
+    const int kc = a.kc_desc ? a.Nc - 1 - kci : kci;
+    const int bh = __builtin_amdgcn_readfirstlane((int)((wg / a.Nc) * bpx + bl));
     const long tbase = (long)bh * a.T + (long)kc * a.L;
     const int r0 = rb * BR, wr0 = r0 + wave * 32;
     const int d2 = a.d2;
