@@ -18,8 +18,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
 # recurrent.hip: MFMA accumulators in ordinary VGPRs (the kernel also scales and stores them with
 # vector ALU instructions, which cannot read accumulation registers)
 UNITS = [("api.hip", "api.o", []), ("gates.hip", "gates.o", []), ("step.hip", "step.o", []), ("norm.hip", "norm.o", []), ("pad.hip", "pad.o", []),
-         ("recurrent.hip", "recurrent.o", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
-         ("tile_walk.hip", "tile_walk.o", ["-mllvm", "-amdgpu-mfma-vgpr-form"])] + [
+         ("recurrent.hip", "recurrent.o", ["-mllvm", "-amdgpu-mfma-vgpr-form"])] + [
     ("tile_inst.hip", "tile_mode%d.o" % m, ["-DTFLA_TILE_MODE=%d" % m]) for m in range(4)]
 
 

@@ -80,7 +80,7 @@ inline int anchor_G(const Dims& d) { return anchor_chunks(d.L, d.dqk > d.dhv ? d
 inline size_t anchor_slots(const Dims& d) { const int G = anchor_G(d); return (size_t)((d.Nc + G - 1) / G); }
 
 struct FwdWs {
-    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *nst, *Cfin, *pacc, *pnrm, *anc;
+    float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *nst, *Cfin, *pacc, *pnrm, *anc, *wrowB, *sQ;
     void* stT;
     size_t bytes;
 };
@@ -89,6 +89,7 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
     FwdWs w;
     w.wrow = c.take<float>(d.BHT); w.ucol = c.take<float>(d.BHT); w.sH = c.take<float>(d.BHT);
     w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
+    w.wrowB = c.take<float>(d.BHT); w.sQ = c.take<float>(d.BHT);     // the backward pass's row weights (mLSTMexp)
     w.gbar = c.take<float>(d.BH * d.Nc);
     w.csum = c.take<float>(2 * d.BH * d.Nc);
     w.nst = c.take<float>(d.BH * d.Nc * d.dqk);
@@ -251,6 +252,7 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     t.wrow = w.wrow; t.wcol = w.ucol; t.srow = w.sH; t.St = w.stT;
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
     t.variant = variant; t.eps = eps; t.nstate = w.nst; t.mout = mout; t.nout = is_exp ? n_out : nullptr;
+    t.wrowB_out = is_exp ? w.wrowB : nullptr; t.sQ_out = is_exp ? w.sQ : nullptr;
     t.dotwith = nullptr; t.dotpart = nullptr; t.E = nullptr;
     TFLA_LAUNCH(K_TILE_H, launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
 
@@ -312,10 +314,21 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
         int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, softcap, Tvalid, dqk_true, s);
         if (st != TFLA_OK) return st;
     }
-    GateBwdPrepArgs p;
-    p.wrow = wrow; p.sH = sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
-    p.n = d.BHT; p.variant = variant; p.eps = eps;
-    TFLA_LAUNCH(K_BWD_PREP, launch_gate_bwd_prep(p, s));
+    // mLSTMsig has no denominator (the weights are the forward pass's own); for mLSTMexp the forward call has left
+    // them in its workspace when it wrote n_out, otherwise they are formed here from n_out and m_out
+    const float* wrowB = wrow;
+    const float* sQ = sH;
+    if (is_exp) {
+        if (reuse) {
+            wrowB = fw.wrowB; sQ = fw.sQ;
+        } else {
+            GateBwdPrepArgs p;
+            p.wrow = wrow; p.sH = sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
+            p.n = d.BHT; p.variant = variant; p.eps = eps;
+            TFLA_LAUNCH(K_BWD_PREP, launch_gate_bwd_prep(p, s));
+            wrowB = w.wrowB; sQ = w.sQ;
+        }
+    }
 
     // 2. the chunk states C_{k-1}
     const void* cstates = reuse_states ? fw.stT : w.cN;
@@ -333,7 +346,7 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
     // 3. backward recurrence: dC_k for every chunk, dC_0 at the end
     RecArgs rb;
-    rb.X = q; rb.Y = dH; rb.rs = w.sQ; rb.gbar = gbar; rb.S0 = dCn;
+    rb.X = q; rb.Y = dH; rb.rs = sQ; rb.gbar = gbar; rb.S0 = dCn;
     rb.stT = w.dcT; rb.stN = tonly ? nullptr : w.dcN; rb.Sfinal = dC0; rb.Sfinal2 = nullptr;
     rb.n0 = nullptr; rb.nst = nullptr; rb.nfinal = nullptr;
     rb.T = T; rb.L = chunk; rb.Nc = d.Nc; rb.d1 = dqk; rb.d2 = dhv; rb.reverse = 1;
@@ -348,15 +361,15 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
     t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr; t.E = w.E; t.E2 = w.E2; t.part_acc = w.pacc;
     // dV: rows = kv index j
-    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = w.dcT;
+    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = ucol; t.wcol = wrowB; t.srow = aK; t.St = w.dcT;
     t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
     TFLA_LAUNCH(K_TILE_DV, launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
     // dQ: rows = query index i
-    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = w.wrowB; t.wcol = ucol; t.srow = w.sQ; t.St = cstates;
+    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = wrowB; t.wcol = ucol; t.srow = sQ; t.St = cstates;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = q; t.dotpart = w.partQ;
     TFLA_LAUNCH(K_TILE_DQ, launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
     // dK: rows = kv index j
-    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = ucol; t.wcol = w.wrowB; t.srow = aK; t.St = tonly ? w.dcT : w.dcN;
+    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = ucol; t.wcol = wrowB; t.srow = aK; t.St = tonly ? w.dcT : w.dcN;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = k; t.dotpart = w.partK;
     TFLA_LAUNCH(K_TILE_DK, launch_tile_mode<MODE_DK>(t, (int)d.BH, dtype, s));
 

@@ -80,17 +80,6 @@ __device__ __forceinline__ void dma4(const void* gbase_uniform, uint32_t voff, u
                  :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
 }
 
-// dma4 without the "memory" clobber (see dma16_free)
-__device__ __forceinline__ void dma4_free(const void* gbase_uniform, uint32_t voff, uint32_t lds_uniform) {
-    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_uniform);
-    const uint64_t gb = (uint64_t)(uintptr_t)gbase_uniform;
-    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
-    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
-    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dword %1, %2"
-                 :: "s"(la), "v"(voff), "s"(gu) : "m0");
-}
-
 // workgroup barrier without the fence a __syncthreads() carries (that fence would wait for
 // every outstanding global->LDS load, i.e. drain the pipeline)
 __device__ __forceinline__ void barrier_nofence() { asm volatile("s_barrier" ::: "memory"); }
@@ -134,14 +123,6 @@ template <int ROWS, int COLS, int NT, int KIND> struct DmaTile {
         const int wave = tid >> 6;
 #pragma unroll
         for (int j = 0; j < N; ++j) dma16(gtile, goff[j], lds + (wave + j * NWV) * 1024);
-    }
-    // load j only (j compile-time in the callers; j >= N issues nothing), without the "memory" clobber: for loads
-    // placed between matrix instructions into a stage nobody reads in that phase
-    __device__ __forceinline__ void issue_one(const bf16_t* gtile, uint32_t lds, int tid, int j) const {
-        const int wave = tid >> 6;
-#pragma unroll
-        for (int q = 0; q < N; ++q)
-            if (q == j) dma16_free(gtile, goff[q], lds + (wave + q * NWV) * 1024);
     }
     // the loads j = part, part + nparts, ... only (part, nparts compile-time in the callers)
     __device__ __forceinline__ void issue_part(const bf16_t* gtile, uint32_t lds, int tid, int part, int nparts) const {

@@ -165,6 +165,9 @@ struct TileArgs {
     const float* nstate;            // (BH, Nc, d1); bf16 kernels: (BH, Nc, 2, d1) bf16 as RecArgs::nst
     const float* mout;              // (BH, T)
     float* nout;                    // (BH, T) or NULL
+    // MODE_H, mLSTMexp: the backward pass's row weights with 1 / h_denom folded in (what gate_bwd_prep_kernel
+    // computes from n_out and m_out), written here while the denominator is at hand; (BH, T) each, or NULL
+    float* wrowB_out; float* sQ_out;
     // MODE_DQ / MODE_DK: partial row dots  sum_n out[r,n] * dotwith[r,n]
     const void* dotwith;            // (BH, T, d2)
     float* dotpart;                 // (d2/BD2, BH*T)
@@ -180,10 +183,6 @@ struct TileArgs {
     float* acc_out; float* nrm_out;             // store the raw accumulators / normaliser instead of the output
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
-// bf16 H and dV (mode MODE_H / MODE_DV) with one workgroup per 256 rows that walks all column blocks (tile_walk.h):
-// contraction widths 128 and 256, output widths that are multiples of 128, chunks that are multiples of 256
-inline bool tile_walk_supported(int d1, int d2, int L) { return (d1 == 128 || d1 == 256) && d2 % 128 == 0 && L % 256 == 0; }
-hipError_t launch_tile_walk(const TileArgs& a, int mode, int BH, hipStream_t s);
 // d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16
 // wavefront within 256 registers, so that two workgroups share a CU when d1 <= 256.  The bf16 dQ and
 // dK kernels take a 256-wide block when d1 = 512 (one workgroup per CU anyway): half as many

@@ -214,6 +214,10 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
             if (g == 0) {
                 ldsR[wave * 32 + l32] = 1.0f / den;
                 if (a.nout && nb2 == 0) a.nout[t] = nrm;
+                if (a.wrowB_out && nb2 == 0) {
+                    a.wrowB_out[t] = a.wrow[t] - log2f(den);
+                    a.sQ_out[t] = a.srow[t] / den;
+                }
             }
             __syncthreads();
 #pragma unroll
@@ -312,13 +316,6 @@ hipError_t launch_tile_mode(const TileArgs& a0, int BH, int dtype, hipStream_t s
 #endif
     a.kc_desc = ((TFLA_KC_ORDER) >> MODE) & 1;
     const int bd2 = tile_bd2(a.d1, a.d2, dtype, MODE, a.L);
-    // H and dV at contraction widths 128 / 256 with chunks that are multiples of 256: one workgroup per 256 rows
-    // walks all column blocks (tile_walk.h)
-#ifdef TFLA_USE_WALK
-    if constexpr (MODE == MODE_H || MODE == MODE_DV) {
-        if (dtype == 1 && tile_width_override == 0 && tile_walk_supported(a.d1, a.d2, a.L)) return launch_tile_walk(a, MODE, BH, s);
-    }
-#endif
     if (dtype != 1) return a.d1 > 256 ? hipErrorInvalidValue : launch_tile_m<float, MODE>(a, BH, bd2, s);
     if (a.d1 <= 512) return launch_tile_m<bf16_t, MODE>(a, BH, bd2, s);
     // d1 = 1024: the kernels hold a workgroup's X rows in registers, which ends at 512 columns.  Every term of

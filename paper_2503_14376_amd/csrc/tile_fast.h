@@ -500,6 +500,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             const float den = fmaxf(fabsf(nrm), expf(-ldsM[wave][l32])) + a.eps;
             inv = 1.0f / den;
             if (g == 0 && a.nout && nb2 == 0) a.nout[t] = nrm;
+            if (g == 0 && a.wrowB_out && nb2 == 0) {
+                a.wrowB_out[t] = wr - log2f(den);
+                a.sQ_out[t] = srl / den;
+            }
         }
     }
     // Register quad 4j..4j+3 of block nb holds columns 32 nb + 8 j + 4 g + {0..3} of row t.  The
