@@ -59,6 +59,12 @@ def algorithmic_bytes(w: wl.Workload, es: int):
     st = w.B * w.NH * (w.T // w.chunk) * w.dqk * w.dhv * es
     g = tok * 4
     rec = tok * (w.dqk + w.dhv) * es + st + 2 * g
+    if es == 2:
+        # fp32 copies of the state at the block boundaries of the anchored forget-gate gradient scan (every fourth
+        # chunk, blocks of at most 2048 steps): the forward launch writes them, the reversed launch reads them
+        nc = w.T // w.chunk
+        G = 4 if 4 * w.chunk <= 2048 else max(1, 2048 // w.chunk)
+        rec += w.B * w.NH * max(0, (nc + G - 1) // G - 1) * w.dqk * w.dhv * 4
     etri = tok * w.chunk * es // 2     # the weighted intra-chunk matrix E, lower triangle: dQ writes it, dK reads it
     return {
         "recurrent_fwd": rec,

@@ -122,6 +122,30 @@ def test_relatives_through_the_same_kernel():
         assert gu.rel_err(f["H"][0, h], ref) <= 1e-4, h
 
 
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
+@pytest.mark.parametrize("relative", ["decay_only", "input_gate_only", "plain_linear_attention"])
+def test_relatives_forward_and_backward(dtype, relative):
+    """The scalar-gate relatives of Sec. 5 / App. A.2 through the mLSTMsig entry points, forward and backward, in both
+    element types, against the fp64 oracle on the same gate values: a constant decay per head with the input gate
+    fixed to one (retention / simple gated linear attention), a data-dependent input gate without forgetting, and
+    no gates at all (causal linear attention).  A gate "fixed to one" is a pre-activation of +40 (sigma = 1 to fp32
+    precision); its gradient is then of order sigma(-40) and is compared like any other output."""
+    w = wl.small(wl.SIG, dtype, B=1, NH=4, T=512, dqk=128, dhv=128, chunk=128, seed=83, init_state=False)
+    d = wl.make_inputs(w)
+    if relative == "decay_only":
+        gammas = np.array([0.5, 0.9, 0.97, 0.995])
+        d["i_pre"][:] = 40.0
+        d["f_pre"][:] = np.log(gammas / (1 - gammas)).astype(np.float32)[None, :, None]
+    elif relative == "input_gate_only":
+        d["f_pre"][:] = 40.0
+    else:
+        d["i_pre"][:] = 40.0
+        d["f_pre"][:] = 40.0
+        # without decay the sums grow with t: scale the values so that bf16 outputs stay well inside the format
+        d["v"] = wl.bf16_round(d["v"] * np.float32(0.25)) if dtype == wl.BF16 else d["v"] * np.float32(0.25)
+    _fwd_bwd(w, d)
+
+
 @pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
 @pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
 @pytest.mark.parametrize("T,chunk", [(1, 64), (63, 64), (100, 64), (200, 64), (449, 128), (1000, 256)])
