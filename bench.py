@@ -63,16 +63,20 @@ def algorithmic_bytes(w: wl.Workload, es: int):
         # fp32 copies of the state at the block boundaries of the anchored forget-gate gradient scan (every fourth
         # chunk, blocks of at most 2048 steps): the forward launch writes them, the reversed launch reads them
         nc = w.T // w.chunk
-        G = 4 if 4 * w.chunk <= 2048 else max(1, 2048 // w.chunk)
+        G = 1 if max(w.dqk, w.dhv) > 512 else (4 if 4 * w.chunk <= 2048 else max(1, 2048 // w.chunk))
         rec += w.B * w.NH * max(0, (nc + G - 1) // G - 1) * w.dqk * w.dhv * 4
-    etri = tok * w.chunk * es // 2     # the weighted intra-chunk matrix E, lower triangle: dQ writes it, dK reads it
+    # the weighted intra-chunk matrix E, lower triangle: where the contraction over d_hv is wider than 256 columns
+    # (bf16 path) dQ writes it and dK reads it instead of dH; narrower heads recompute it in dK
+    shares_e = es == 2 and w.dhv > 256
+    etri = tok * w.chunk * es // 2 if shares_e else 0
+    dk_in = etri if shares_e else tok * w.dhv * es
     return {
         "recurrent_fwd": rec,
         "recurrent_bwd": rec,
         "tile_H": tok * (2 * w.dqk + w.dhv) * es + st + tok * w.dhv * es + 4 * g,
         "tile_dV": tok * (2 * w.dqk + w.dhv) * es + st + tok * w.dhv * es + 3 * g,
         "tile_dQ": tok * (2 * w.dhv + 2 * w.dqk) * es + st + tok * w.dqk * es + etri + 4 * g,
-        "tile_dK": tok * (w.dhv + 2 * w.dqk) * es + st + tok * w.dqk * es + etri + 4 * g,
+        "tile_dK": tok * (w.dhv + 2 * w.dqk) * es + st + tok * w.dqk * es + dk_in + 4 * g,
     }
 
 

@@ -130,7 +130,7 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     w.cN = c.take_bytes(st); w.dcT = c.take_bytes(st);
     w.dcN = d.dtype == TFLA_BF16 ? nullptr : c.take_bytes(st);
     // bf16: the weighted intra-chunk matrix shared by dQ and dK, (BH, Nc, L, L)
-    w.E = d.dtype == TFLA_BF16 ? c.take_bytes((size_t)d.BHT * d.L * d.esz) : nullptr;
+    w.E = (d.dtype == TFLA_BF16 && tile_shares_E(d.dhv)) ? c.take_bytes((size_t)d.BHT * d.L * d.esz) : nullptr;
     // head dimensions above 512: fp32 partial results of the gradient kernels' first half, and the second
     // half's E when the products of dQ / dK run over the halves of d_hv
     const int dwide = d.dqk > d.dhv ? d.dqk : d.dhv;

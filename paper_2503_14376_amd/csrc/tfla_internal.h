@@ -147,6 +147,15 @@ struct RecArgs {
     float* anc; const float* anc_in; float* anc_part; int anc_G;
 };
 hipError_t launch_recurrent(const RecArgs& a, int BH, int dtype, hipStream_t s);
+// dQ and dK weight the same matrix dH V^T.  Where the contraction that forms it (over d_hv) is wider than this, the dQ
+// kernel stores its weighted tiles E (L x L per chunk) and the dK kernel reads them; up to this width both kernels
+// form the matrix themselves, because E is then more bytes than the operands it replaces (measured at
+// d_hv = 64 / 128 / 256: -19 % / -8 % / -1 % per step without E; at 512: +3 %).
+#ifndef TFLA_NOE_MAX_D1
+#define TFLA_NOE_MAX_D1 256
+#endif
+inline bool tile_shares_E(int dhv) { return dhv > TFLA_NOE_MAX_D1; }
+
 inline int rec_anchor_parts(int d1, int d2) { return (d1 / 64) * (d2 / 32); }
 
 // ---- intra-chunk tiled kernels (Sec. 3, App. C.3 Alg. 1, App. C.4) ---------------------------

@@ -254,7 +254,9 @@ static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
     if constexpr (sizeof(DT) == 2) {
         // two workgroups per CU when the accumulator is narrow enough for 256 registers per lane
         constexpr int OCC = (BD2 <= 128 && D1 <= 256) ? 2 : 1;
-        hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT>), grid, dim3(64 * NW), 0, s, a);
+        // dQ / dK share the weighted matrix E through memory only where the contraction that forms it is wide
+        constexpr int NOE = ((MODE == MODE_DQ || MODE == MODE_DK) && D1 <= TFLA_NOE_MAX_D1) ? 1 : 0;
+        hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT, NOE>), grid, dim3(64 * NW), 0, s, a);
     } else {
         constexpr int BC = 32;   // two LDS stages must fit in 160 KB
         hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE>), grid, dim3(64 * NW), 0, s, a);

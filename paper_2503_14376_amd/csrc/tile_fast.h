@@ -29,14 +29,16 @@ static __device__ unsigned long long tfla_timeline[1 << 18];
 // SPLIT: 0 = the whole contraction over D1 in this launch; 1 / 2 = the first / second 512-wide half of a
 // contraction over 1024 columns (rows of the D1-wide operands are 2 D1 apart): the first half stores its raw fp32
 // accumulators, the second adds them to its own before the epilogue.
-template <int D1, int BD2, int NW, int MODE, int OCC, int SPLIT = 0>
+// NOE: 1 = the dQ kernel does not store the weighted matrix E and the dK kernel recomputes it from dH and V
+// like every other mode (narrow contractions: E, L x L per chunk, is then more bytes than the operands it replaces).
+template <int D1, int BD2, int NW, int MODE, int OCC, int SPLIT = 0, int NOE = 0>
 __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     using E = Elem<bf16_t>;
     using frag = E::frag;
     constexpr bool UPPER = (MODE & 1) != 0;
     constexpr bool STT = (MODE == MODE_DQ || MODE == MODE_DK);   // state slices are contraction-major
-    constexpr bool ELITE = MODE == MODE_DK;                      // column tiles carry E instead of Y
-    constexpr bool EWRITE = MODE == MODE_DQ;
+    constexpr bool ELITE = MODE == MODE_DK && !NOE;              // column tiles carry E instead of Y
+    constexpr bool EWRITE = MODE == MODE_DQ && !NOE;
     constexpr int NT = NW * 64, BR = NW * 32, BC = 32;
     constexpr int KS1 = D1 / 16, NB = BD2 / 32;
     constexpr int YB = ELITE ? BC * BR * 2 : BC * D1 * 2, ZB = BC * BD2 * 2;         // bytes
