@@ -27,7 +27,7 @@
  *    nn, mn, n_out, m_out are filled with zeros when non-NULL.
  *  - eps is added to the denominator max{|n^T q~|, exp(-m)}; eps = 0 is the paper's formula.
  *  - Restrictions: chunk % 64 == 0, 64 <= chunk <= 2048, ceil(T / chunk) <= 4096, dqk and dhv
- *    multiples of 8, at most 1024 (at most 256 for TFLA_F32),
+ *    multiples of 8, at most 1024 (at most 512 for TFLA_F32),
  *    B * NH <= 65535.
  *  - T need not be a multiple of chunk (N_c = ceil(T / chunk), Sec. 2.2), and the head dimensions need
  *    not be among the kernels' own widths 64, 128, 256, 512, 1024.  The kernels work on whole chunks and on

@@ -23,6 +23,8 @@ struct Dims {
 };
 
 // the head dimension the kernels run a caller's head dimension at (zero-padded columns in between)
+// a contraction wider than the tiled kernels hold in registers runs as two launches that meet in fp32
+inline bool contraction_split(int d1, int dtype) { return dtype == TFLA_BF16 ? d1 > 512 : d1 > 256; }
 inline int kernel_dim(int d) { return d <= 64 ? 64 : (d <= 128 ? 128 : (d <= 256 ? 256 : (d <= 512 ? 512 : 1024))); }
 
 // core = true: the kernels' own widths only (what the kernel sequences are called with)
@@ -31,7 +33,7 @@ int check_dims(int direction, int B, int NH, int T, int dqk, int dhv, int chunk,
     if (variant != TFLA_EXP && variant != TFLA_SIG) return TFLA_ERR_ENUM;
     if (dtype != TFLA_F32 && dtype != TFLA_BF16) return TFLA_ERR_ENUM;
     if (B <= 0 || NH <= 0 || T <= 0 || dqk <= 0 || dhv <= 0) return TFLA_ERR_SHAPE;
-    const int dmax = dtype == TFLA_BF16 ? 1024 : 256;
+    const int dmax = dtype == TFLA_BF16 ? 1024 : 512;
     auto ok_d = [&](int d) {
         if (d > dmax || d % 8 != 0) return false;
         return !core || d == 64 || d == 128 || d == 256 || d == 512 || d == 1024;
@@ -96,8 +98,8 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
     w.Cfin = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
     w.stT = c.take_bytes((size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz);
     // d_qk above 512: the parallel kernel contracts over d_qk in two halves that meet in fp32
-    w.pacc = d.dqk > 512 ? c.take<float>((size_t)d.BHT * d.dhv) : nullptr;
-    w.pnrm = d.dqk > 512 ? c.take<float>(d.BHT) : nullptr;
+    w.pacc = contraction_split(d.dqk, d.dtype) ? c.take<float>((size_t)d.BHT * d.dhv) : nullptr;
+    w.pnrm = contraction_split(d.dqk, d.dtype) ? c.take<float>(d.BHT) : nullptr;
     // bf16: fp32 copies of the state at the block boundaries of the forget-gate gradient scan (see bwd_core)
     w.anc = d.dtype == TFLA_BF16 ? c.take<float>(anchor_slots(d) * (size_t)d.BH * d.dqk * d.dhv) : nullptr;
     w.bytes = c.off;
@@ -134,7 +136,7 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     // head dimensions above 512: fp32 partial results of the gradient kernels' first half, and the second
     // half's E when the products of dQ / dK run over the halves of d_hv
     const int dwide = d.dqk > d.dhv ? d.dqk : d.dhv;
-    w.pacc = dwide > 512 ? c.take<float>((size_t)d.BHT * dwide) : nullptr;
+    w.pacc = contraction_split(dwide, d.dtype) ? c.take<float>((size_t)d.BHT * dwide) : nullptr;
     w.E2 = (d.dtype == TFLA_BF16 && d.dhv > 512) ? c.take_bytes((size_t)d.BHT * d.L * d.esz) : nullptr;
     // bf16: fp32 boundary copies of C (used when the states are recomputed here), and the partial inner products
     // <C, dC> of every boundary

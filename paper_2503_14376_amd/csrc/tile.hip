@@ -28,7 +28,9 @@ namespace tfla {
 
 // Generic kernel (any element type; operands staged through registers).  bf16 uses
 // tile_kernel_bf16 (tile_fast.h); this one serves fp32.
-template <typename DT, int D1, int BD2, int BC, int NW, int MODE>
+// SPLIT as in tile_kernel_bf16: 1 / 2 = the first / second D1-wide half of a contraction over 2 D1 columns (rows of
+// X, Y and the state are 2 D1 apart); the first half stores its raw accumulators, the second adds them to its own.
+template <typename DT, int D1, int BD2, int BC, int NW, int MODE, int SPLIT = 0>
 __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     using E = Elem<DT>;
     using frag = typename E::frag;
@@ -36,6 +38,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     constexpr int NT = NW * 64, BR = NW * 32;
     constexpr int KS1 = D1 / 16, NB = BD2 / 32, NK = D1 / BC;
     constexpr int YS = D1 + E::PAD, ZS = BC + E::PAD;
+    constexpr int ld1 = SPLIT ? 2 * D1 : D1;    // row stride of the operands with D1 columns
     // two stages of (Y tile, Z tile, column weights): one is multiplied while the other is filled
     __shared__ __attribute__((aligned(16))) DT ldsY[2][BC * YS];
     __shared__ __attribute__((aligned(16))) DT ldsZ[2][BD2 * ZS];
@@ -62,21 +65,21 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     const int d2 = a.d2;
 
     const DT* X = reinterpret_cast<const DT*>(a.X);
-    const DT* Y = reinterpret_cast<const DT*>(a.Y) + tbase * D1;
+    const DT* Y = reinterpret_cast<const DT*>(a.Y) + tbase * ld1;
     const DT* Z = reinterpret_cast<const DT*>(a.Z) + tbase * d2 + (long)nb2 * BD2;
-    const DT* St = reinterpret_cast<const DT*>(a.St) + (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * D1;
+    const DT* St = reinterpret_cast<const DT*>(a.St) + (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * ld1;
     const float* wcol = a.wcol + tbase;
 
     // X fragments of the wavefront's 32 rows (lane: row l32, k-group g)
     frag xf[KS1];
     {
-        const DT* xr = X + (tbase + wr0 + l32) * D1 + 8 * g;
+        const DT* xr = X + (tbase + wr0 + l32) * ld1 + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks) xf[ks] = E::load(xr + 16 * ks);
     }
     if (MODE == MODE_H) {
         if (a.variant == 0)
-            for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * D1 + i];
+            for (int i = tid; i < D1; i += NT) ldsN[i] = a.nstate[((long)bh * a.Nc + kc) * ld1 + i];
     }
 
     f32x16 acc[NB];
@@ -95,15 +98,15 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     int buf = 0;
 
     // ---------------- inter-chunk part: acc = X_r St, BC columns of d1 per stage
-    ps.load(St, D1, tid);
+    ps.load(St, ld1, tid);
     ps.store(ldsZ[0], ZS, tid);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NK; ++j) {
         if (j + 1 < NK) {
-            ps.load(St + (j + 1) * BC, D1, tid);
+            ps.load(St + (j + 1) * BC, ld1, tid);
         } else {
-            py.load(Y + (long)ct_lo * BC * D1, D1, tid);
+            py.load(Y + (long)ct_lo * BC * ld1, ld1, tid);
             pz.load(Z + (long)ct_lo * BC * d2, d2, tid);
             if (tid < BC) pw = wcol[ct_lo * BC + tid];
         }
@@ -154,7 +157,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
         const int c0 = ct * BC;
         const bool more = ct + 1 < ct_hi;
         if (more) {
-            py.load(Y + (long)(c0 + BC) * D1, D1, tid);
+            py.load(Y + (long)(c0 + BC) * ld1, ld1, tid);
             pz.load(Z + (long)(c0 + BC) * d2, d2, tid);
             if (tid < BC) pw = wcol[c0 + BC + tid];
         }
@@ -209,6 +212,32 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
         if (a.variant == 0) {
             rowsum += __shfl_xor(rowsum, 32, 64);
             nrm += rowsum;
+        }
+    }
+    if constexpr (SPLIT == 1) {
+        // first half: raw accumulators (and this half's share of the normaliser) for the second launch
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const long t = tbase + wr0 + acc_row(v, g);
+                a.acc_out[t * d2 + (long)nb2 * BD2 + nb * 32 + l32] = acc[nb][v];
+            }
+        if (MODE == MODE_H && a.variant == 0 && g == 0 && nb2 == 0) a.nrm_out[tbase + wr0 + l32] = nrm;
+        return;
+    }
+    if constexpr (SPLIT == 2) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const long t = tbase + wr0 + acc_row(v, g);
+                acc[nb][v] += a.acc_in[t * d2 + (long)nb2 * BD2 + nb * 32 + l32];
+            }
+        if (MODE == MODE_H && a.variant == 0) nrm += a.nrm_in[tbase + wr0 + l32];
+    }
+    if (MODE == MODE_H) {
+        if (a.variant == 0) {
             const long t = tbase + wr0 + l32;
             const float den = fmaxf(fabsf(nrm), expf(-a.mout[t])) + a.eps;
             if (g == 0) {
@@ -259,23 +288,23 @@ static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
         hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT, NOE>), grid, dim3(64 * NW), 0, s, a);
     } else {
         constexpr int BC = 32;   // two LDS stages must fit in 160 KB
-        hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE>), grid, dim3(64 * NW), 0, s, a);
+        hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE, SPLIT>), grid, dim3(64 * NW), 0, s, a);
     }
     return hipGetLastError();
 }
 
-template <typename DT, int D1, int MODE>
+template <typename DT, int D1, int MODE, int SPLIT = 0>
 static hipError_t launch_tile_d1(const TileArgs& a, int BH, int bd2, hipStream_t s) {
     if (a.L % 128 == 0) {
-        if constexpr (sizeof(DT) == 2 && D1 > 256) {
+        if constexpr (sizeof(DT) == 2 && D1 > 256 && SPLIT == 0) {
             if (bd2 == 256) return launch_tile_t<DT, D1, 256, 4, MODE>(a, BH, s);
         }
-        if (bd2 == 128) return launch_tile_t<DT, D1, 128, 4, MODE>(a, BH, s);
-        if (bd2 == 64) return launch_tile_t<DT, D1, 64, 4, MODE>(a, BH, s);
+        if (bd2 == 128) return launch_tile_t<DT, D1, 128, 4, MODE, SPLIT>(a, BH, s);
+        if (bd2 == 64) return launch_tile_t<DT, D1, 64, 4, MODE, SPLIT>(a, BH, s);
         return hipErrorInvalidValue;    // the caller sized its buffers for a block width that is not built
     }
-    if (bd2 == 128) return launch_tile_t<DT, D1, 128, 2, MODE>(a, BH, s);
-    if (bd2 == 64) return launch_tile_t<DT, D1, 64, 2, MODE>(a, BH, s);
+    if (bd2 == 128) return launch_tile_t<DT, D1, 128, 2, MODE, SPLIT>(a, BH, s);
+    if (bd2 == 64) return launch_tile_t<DT, D1, 64, 2, MODE, SPLIT>(a, BH, s);
     return hipErrorInvalidValue;
 }
 
@@ -293,17 +322,10 @@ static hipError_t launch_tile_m(const TileArgs& a, int BH, int bd2, hipStream_t 
     return hipErrorInvalidValue;
 }
 
-// one 512-wide half (SPLIT = 1, 2) of a contraction over 1024 columns
+// one 512-wide half (SPLIT = 1, 2) of a bf16 contraction over 1024 columns
 template <int MODE, int SPLIT>
 static hipError_t launch_tile_half(const TileArgs& a, int BH, int bd2, hipStream_t s) {
-    if (a.L % 128 == 0) {
-        if (bd2 == 128) return launch_tile_t<bf16_t, 512, 128, 4, MODE, SPLIT>(a, BH, s);
-        if (bd2 == 64) return launch_tile_t<bf16_t, 512, 64, 4, MODE, SPLIT>(a, BH, s);
-        return hipErrorInvalidValue;
-    }
-    if (bd2 == 128) return launch_tile_t<bf16_t, 512, 128, 2, MODE, SPLIT>(a, BH, s);
-    if (bd2 == 64) return launch_tile_t<bf16_t, 512, 64, 2, MODE, SPLIT>(a, BH, s);
-    return hipErrorInvalidValue;
+    return launch_tile_d1<bf16_t, 512, MODE, SPLIT>(a, BH, bd2, s);
 }
 
 template <int MODE>
@@ -318,7 +340,25 @@ hipError_t launch_tile_mode(const TileArgs& a0, int BH, int dtype, hipStream_t s
 #endif
     a.kc_desc = ((TFLA_KC_ORDER) >> MODE) & 1;
     const int bd2 = tile_bd2(a.d1, a.d2, dtype, MODE, a.L);
-    if (dtype != 1) return a.d1 > 256 ? hipErrorInvalidValue : launch_tile_m<float, MODE>(a, BH, bd2, s);
+    const bool nrm = MODE == MODE_H && a.variant == 0;
+    if (dtype != 1) {
+        if (a.d1 <= 256) return launch_tile_m<float, MODE>(a, BH, bd2, s);
+        // fp32, d1 = 512: a wavefront's rows of X fill the register file at 256 fp32 columns, so the contraction runs
+        // as two 256-wide launches that meet in fp32, exactly like the 1024-wide bf16 case below
+        if (a.d1 != 512 || !a.part_acc || (nrm && !a.part_nrm)) return hipErrorInvalidValue;
+        TileArgs h = a;
+        h.d1 = 256;
+        h.acc_out = a.part_acc; h.nrm_out = a.part_nrm;
+        hipError_t e = launch_tile_d1<float, 256, MODE, 1>(h, BH, bd2, s);
+        if (e != hipSuccess) return e;
+        h.acc_out = nullptr; h.nrm_out = nullptr;
+        h.acc_in = a.part_acc; h.nrm_in = a.part_nrm;
+        h.X = reinterpret_cast<const float*>(a.X) + 256;
+        h.Y = reinterpret_cast<const float*>(a.Y) + 256;
+        h.St = reinterpret_cast<const float*>(a.St) + 256;
+        if (a.nstate) h.nstate = a.nstate + 256;
+        return launch_tile_d1<float, 256, MODE, 2>(h, BH, bd2, s);
+    }
     if (a.d1 <= 512) return launch_tile_m<bf16_t, MODE>(a, BH, bd2, s);
     // d1 = 1024: the kernels hold a workgroup's X rows in registers, which ends at 512 columns.  Every term of
     // the result is linear in the products over d1 (the weights depend on the gates only), so the contraction
@@ -326,7 +366,6 @@ hipError_t launch_tile_mode(const TileArgs& a0, int BH, int dtype, hipStream_t s
     // of the normaliser) in fp32, the second adds them to its own before the epilogue.  dQ writes one matrix E
     // per half (its products run over the halves of d_hv); dK reads the matching one in each of its launches.
     constexpr bool STT = (MODE == MODE_DQ || MODE == MODE_DK);
-    const bool nrm = MODE == MODE_H && a.variant == 0;
     if (a.d1 != 1024 || !a.part_acc || (nrm && !a.part_nrm) || (STT && a.E && !a.E2)) return hipErrorInvalidValue;
     TileArgs h = a;
     h.d1 = 512;

@@ -195,9 +195,16 @@ def test_head_dimensions_between_the_kernel_widths(variant, dtype, dqk, dhv, T):
     """Head dimensions that are not 64, 128, 256 or 512 (the paper's head-dimension benchmark starts at 32): forward
     with an initial state, final state, backward -- everything as for the problem as given, 1/sqrt(dqk) of the true dqk
     included."""
-    if dtype == wl.F32 and max(dqk, dhv) > 256:
-        pytest.skip("the fp32 path goes up to 256")
     w = wl.small(variant, dtype, B=1, NH=2, T=T, dqk=dqk, dhv=dhv, chunk=64, seed=85 + dqk + dhv)
+    _fwd_bwd(w, wl.make_inputs(w))
+
+
+@pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
+@pytest.mark.parametrize("dqk,dhv,chunk", [(512, 512, 64), (256, 512, 128), (512, 64, 64)])
+def test_fp32_head_dimensions_up_to_512(variant, dqk, dhv, chunk):
+    """fp32 with 512-wide heads: a contraction over 512 fp32 columns runs as two 256-wide launches that meet in fp32
+    (H and dV when dqk = 512, dQ and dK when dhv = 512).  Initial state, final state, backward, 1e-4."""
+    w = wl.small(variant, wl.F32, B=1, NH=2, T=256, dqk=dqk, dhv=dhv, chunk=chunk, seed=89 + dqk + dhv)
     _fwd_bwd(w, wl.make_inputs(w))
 
 

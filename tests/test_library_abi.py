@@ -69,7 +69,7 @@ def test_check_accepts_the_benchmark_configurations(tfla):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(B=0), -2), (dict(NH=-1), -2), (dict(T=0), -2), (dict(dqk=100), -2), (dict(dqk=4), -2), (dict(dhv=1032), -2), (dict(dqk=2048), -2),
-    (dict(dtype=0, dhv=512), -2), (dict(B=4096, NH=16), -2),
+    (dict(dtype=0, dhv=1024), -2), (dict(B=4096, NH=16), -2),
     (dict(chunk=0), -3), (dict(chunk=32), -3), (dict(chunk=96), -3), (dict(chunk=4096), -3),
     (dict(T=64 * 8192, chunk=64), -3),
     (dict(variant=2), -4), (dict(dtype=7), -4), (dict(direction=3), -4),
