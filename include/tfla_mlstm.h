@@ -89,8 +89,9 @@ enum {
  *        m_t of every step, which tfla_mlstm_bwd needs for TFLA_EXP.
  *   workspace: device scratch of at least tfla_mlstm_workspace_bytes(TFLA_FWD, ...) bytes,
  *        256-byte aligned.  Afterwards it holds, in a layout private to the library, what the
- *        backward pass can reuse (the gate vectors, the chunk states C_{k-1} of Sec. 2.2 and
- *        C_T): a caller that keeps it untouched until the matching tfla_mlstm_bwd call may pass
+ *        backward pass can reuse (the gate vectors, the chunk states C_{k-1} of Sec. 2.2,
+ *        C_T and, where the library padded them, its padded copies of q, k, v and the gate
+ *        pre-activations): a caller that keeps it untouched until the matching tfla_mlstm_bwd call may pass
  *        it there as fwd_workspace; a caller that does not may overwrite or free it.
  */
 TFLA_API int tfla_mlstm_fwd(const void* q, const void* k, const void* v,

@@ -216,8 +216,8 @@ int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float
 
 // Forward pass over whole chunks: T is a multiple of chunk, steps >= Tvalid are padding.
 int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
-             const float* n0, const float* m0, int B, int NH, int T, int Tvalid, int dqk_true, int dqk, int dhv, int chunk,
-             int variant, int dtype, float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
+             const float* n0, const float* m0, int B, int NH, int T, int Tvalid, int dqk_true, int dhv_true, int dqk, int dhv,
+             int chunk, int variant, int dtype, float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
              void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype, true);
     if (rc != TFLA_OK) return rc;
@@ -249,7 +249,7 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
     // 3. parallel kernel
     TileArgs t{};
-    t.X = q; t.Y = k; t.Z = v; t.Out = H;
+    t.X = q; t.Y = k; t.Z = v; t.Out = H; t.out_T = Tvalid; t.out_ld = dhv_true; t.out_cols = dhv_true;
     t.part_acc = w.pacc; t.part_nrm = w.pnrm;
     t.wrow = w.wrow; t.wcol = w.ucol; t.srow = w.sH; t.St = w.stT;
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
@@ -273,8 +273,8 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
 int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
              const float* n0, const float* m0, const float* n_out, const float* m_out, const void* dH, const float* dCn,
-             int B, int NH, int T, int Tvalid, int dqk_true, int dqk, int dhv, int chunk, int variant, int dtype, float eps,
-             float softcap, void* dq,
+             int B, int NH, int T, int Tvalid, int dqk_true, int dhv_true, int dqk, int dhv, int chunk, int variant, int dtype,
+             float eps, float softcap, void* dq,
              void* dk, void* dv, float* d_i_pre, float* d_f_pre, float* dC0, const void* fwd_workspace,
              size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype, true);
@@ -363,11 +363,11 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
     t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr; t.E = w.E; t.E2 = w.E2; t.part_acc = w.pacc;
     // dV: rows = kv index j
-    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.wrow = ucol; t.wcol = wrowB; t.srow = aK; t.St = w.dcT;
+    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.out_T = Tvalid; t.out_ld = dhv_true; t.out_cols = dhv_true; t.wrow = ucol; t.wcol = wrowB; t.srow = aK; t.St = w.dcT;
     t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
     TFLA_LAUNCH(K_TILE_DV, launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
     // dQ: rows = query index i
-    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.wrow = wrowB; t.wcol = ucol; t.srow = sQ; t.St = cstates;
+    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.out_ld = dqk_true; t.out_cols = dqk_true; t.wrow = wrowB; t.wcol = ucol; t.srow = sQ; t.St = cstates;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = q; t.dotpart = w.partQ;
     TFLA_LAUNCH(K_TILE_DQ, launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
     // dK: rows = kv index j
@@ -402,7 +402,7 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 // run the core there (Tvalid = T, the 1/sqrt(dqk) of the true dqk), and copy the true part of the outputs
 // back.  `d` below always describes the padded problem.
 struct PadFwd {
-    void *q, *k, *v, *H;
+    void *q, *k, *v;
     float *ip, *fp, *nout, *mout, *C0, *n0, *Cn, *nn;
     size_t bytes;
 };
@@ -410,7 +410,7 @@ PadFwd carve_pad_fwd(const Dims& d, void* base) {
     Carver c(base);
     PadFwd p;
     p.q = c.take_bytes((size_t)d.BHT * d.dqk * d.esz); p.k = c.take_bytes((size_t)d.BHT * d.dqk * d.esz);
-    p.v = c.take_bytes((size_t)d.BHT * d.dhv * d.esz); p.H = c.take_bytes((size_t)d.BHT * d.dhv * d.esz);
+    p.v = c.take_bytes((size_t)d.BHT * d.dhv * d.esz);
     p.ip = c.take<float>(d.BHT); p.fp = c.take<float>(d.BHT); p.nout = c.take<float>(d.BHT); p.mout = c.take<float>(d.BHT);
     p.C0 = c.take<float>((size_t)d.BH * d.dqk * d.dhv); p.n0 = c.take<float>((size_t)d.BH * d.dqk);
     p.Cn = c.take<float>((size_t)d.BH * d.dqk * d.dhv); p.nn = c.take<float>((size_t)d.BH * d.dqk);
@@ -418,7 +418,7 @@ PadFwd carve_pad_fwd(const Dims& d, void* base) {
     return p;
 }
 struct PadBwd {
-    void *q, *k, *v, *dH, *dq, *dk, *dv;
+    void *q, *k, *v, *dH;
     float *ip, *fp, *nout, *mout, *di, *df, *C0, *n0, *dCn, *dC0;
     size_t bytes;
 };
@@ -427,7 +427,6 @@ PadBwd carve_pad_bwd(const Dims& d, void* base) {
     PadBwd p;
     const size_t sq = (size_t)d.BHT * d.dqk * d.esz, sv = (size_t)d.BHT * d.dhv * d.esz;
     p.q = c.take_bytes(sq); p.k = c.take_bytes(sq); p.v = c.take_bytes(sv); p.dH = c.take_bytes(sv);
-    p.dq = c.take_bytes(sq); p.dk = c.take_bytes(sq); p.dv = c.take_bytes(sv);
     p.ip = c.take<float>(d.BHT); p.fp = c.take<float>(d.BHT); p.nout = c.take<float>(d.BHT); p.mout = c.take<float>(d.BHT);
     p.di = c.take<float>(d.BHT); p.df = c.take<float>(d.BHT);
     const size_t ss = (size_t)d.BH * d.dqk * d.dhv;
@@ -454,7 +453,7 @@ int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
     const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
     if (rc != TFLA_OK) return rc;
     if (!needs_pad(T, dqk, dhv, chunk))
-        return fwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, T, dqk, dqk, dhv, chunk, variant, dtype, eps, softcap, H,
+        return fwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, T, dqk, dhv, dqk, dhv, chunk, variant, dtype, eps, softcap, H,
                         Cn, nn, mn, n_out, m_out, workspace, workspace_bytes, stream);
     if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
     const bool is_exp = variant == TFLA_EXP;
@@ -486,11 +485,11 @@ int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
     }
     float* Cnc = (dpad && Cn) ? p.Cn : Cn;
     float* nnc = (dpad && nn) ? p.nn : nn;
-    const int st = fwd_core(p.q, p.k, p.v, p.ip, p.fp, C0c, n0c, m0, B, NH, Tp, T, dqk, dq_p, dv_p, chunk, variant, dtype, eps,
-                            softcap, p.H, Cnc, nnc, mn, n_out ? p.nout : nullptr, m_out ? p.mout : nullptr, workspace,
+    // (the H kernel stores the true steps and columns straight into the caller's H)
+    const int st = fwd_core(p.q, p.k, p.v, p.ip, p.fp, C0c, n0c, m0, B, NH, Tp, T, dqk, dhv, dq_p, dv_p, chunk, variant, dtype, eps,
+                            softcap, H, Cnc, nnc, mn, n_out ? p.nout : nullptr, m_out ? p.mout : nullptr, workspace,
                             core_bytes, stream);
     if (st != TFLA_OK) return st;
-    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.H, H, d.BH, T, Tp, dhv * es, dv_p * es, s));
     if (n_out) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.nout, n_out, d.BH, T, Tp, s));
     if (m_out) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.mout, m_out, d.BH, T, Tp, s));
     if (dpad && Cn) TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.Cn, Cn, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
@@ -506,7 +505,7 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
     const int rc = check_dims(TFLA_BWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
     if (rc != TFLA_OK) return rc;
     if (!needs_pad(T, dqk, dhv, chunk))
-        return bwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, n_out, m_out, dH, dCn, B, NH, T, T, dqk, dqk, dhv, chunk, variant,
+        return bwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, n_out, m_out, dH, dCn, B, NH, T, T, dqk, dhv, dqk, dhv, chunk, variant,
                         dtype, eps, softcap, dq, dk, dv, d_i_pre, d_f_pre, dC0, fwd_workspace, fwd_workspace_bytes,
                         workspace, workspace_bytes, stream);
     if (!q || !k || !v || !i_pre || !f_pre || !dH || !dq || !dk || !dv || !d_i_pre || !d_f_pre) return TFLA_ERR_NULL;
@@ -531,12 +530,22 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const int Tp = d.T, es = (int)d.esz, eq = dqk * es, ev = dhv * es, eqp = dq_p * es, evp = dv_p * es;
     const bool dpad = dq_p != dqk || dv_p != dhv;
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, eq, eqp, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, eq, eqp, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, ev, evp, s));
+    // The forward call left its padded copies of q, k, v and the gate pre-activations behind its core workspace:
+    // a backward call that is handed that workspace (whole) reads them there instead of copying again.
+    const void *pq = p.q, *pk = p.k, *pv = p.v;
+    const float *pip = p.ip, *pfp = p.fp;
+    const size_t fwd_core_bytes = carve_fwd(d, nullptr).bytes;
+    if (fwd_workspace && fwd_workspace_bytes >= fwd_core_bytes + carve_pad_fwd(d, nullptr).bytes) {
+        const PadFwd pf = carve_pad_fwd(d, const_cast<char*>(reinterpret_cast<const char*>(fwd_workspace)) + fwd_core_bytes);
+        pq = pf.q; pk = pf.k; pv = pf.v; pip = pf.ip; pfp = pf.fp;
+    } else {
+        TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, eq, eqp, s));
+        TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, eq, eqp, s));
+        TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, ev, evp, s));
+        TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
+        TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
+    }
     TFLA_LAUNCH(K_PAD, launch_pad_rows(dH, p.dH, d.BH, T, Tp, ev, evp, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
     if (is_exp) {
         // denominators of the padding steps: max{|1|, exp(0)} -- any finite non-zero value would do
         TFLA_LAUNCH(K_PAD, launch_pad_scalar(n_out, p.nout, d.BH, T, Tp, 1.0f, s));
@@ -553,13 +562,11 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
         dCnc = p.dCn;
     }
     float* dC0c = (dpad && dC0) ? p.dC0 : dC0;
-    const int st = bwd_core(p.q, p.k, p.v, p.ip, p.fp, C0c, n0c, m0, is_exp ? p.nout : nullptr, is_exp ? p.mout : nullptr,
-                            p.dH, dCnc, B, NH, Tp, T, dqk, dq_p, dv_p, chunk, variant, dtype, eps, softcap, p.dq, p.dk, p.dv,
+    const int st = bwd_core(pq, pk, pv, pip, pfp, C0c, n0c, m0, is_exp ? p.nout : nullptr, is_exp ? p.mout : nullptr,
+                            p.dH, dCnc, B, NH, Tp, T, dqk, dhv, dq_p, dv_p, chunk, variant, dtype, eps, softcap, dq, dk, dv,
                             p.di, p.df, dC0c, fwd_workspace, fwd_workspace_bytes, workspace, core_bytes, stream);
     if (st != TFLA_OK) return st;
-    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dq, dq, d.BH, T, Tp, eq, eqp, s));
-    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dk, dk, d.BH, T, Tp, eq, eqp, s));
-    TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dv, dv, d.BH, T, Tp, ev, evp, s));
+    // (the gradient kernels stored the true steps and columns straight into the caller's dq, dk, dv)
     TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.di, d_i_pre, d.BH, T, Tp, s));
     TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.df, d_f_pre, d.BH, T, Tp, s));
     if (dpad && dC0) TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dC0, dC0, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));

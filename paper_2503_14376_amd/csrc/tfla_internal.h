@@ -164,7 +164,7 @@ inline int rec_anchor_parts(int d1, int d2) { return (d1 / 64) * (d2 / 32); }
 enum { MODE_H = 0, MODE_DV = 1, MODE_DQ = 2, MODE_DK = 3 };
 struct TileArgs {
     const void* X; const void* Y;   // (BH, T, d1)
-    const void* Z; void* Out;       // (BH, T, d2)
+    const void* Z; void* Out;       // Z: (BH, T, d2); Out: (BH, out_T, out_ld), see below
     const float* wrow; const float* wcol; const float* srow;   // (BH, T)
     const void* St;                 // (BH, Nc, d2, d1)
     int T, L, Nc, d1, d2;
@@ -190,6 +190,10 @@ struct TileArgs {
     void* E2;                       // the second half's E (MODE_DQ writes, MODE_DK reads)
     const float* acc_in; const float* nrm_in;   // add these to the accumulators / normaliser before the epilogue
     float* acc_out; float* nrm_out;             // store the raw accumulators / normaliser instead of the output
+    // The output goes straight into the caller's tensor also when the kernels run on a zero-padded copy of the
+    // problem: only steps t < out_T and columns < out_cols are stored, rows are out_ld elements apart
+    // (out_T = T, out_ld = out_cols = d2 when nothing is padded).  out_cols is a multiple of 8.
+    int out_T, out_ld, out_cols;
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
 // d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16

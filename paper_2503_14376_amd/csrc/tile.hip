@@ -258,8 +258,10 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const long t = tbase + wr0 + acc_row(v, g);
-            Out[t * d2 + (long)nb2 * BD2 + nb * 32 + l32] = E::from_f32(acc[nb][v] * inv[v]);
+            // straight into the caller's tensor: its own row count and row length, true steps and columns only
+            const int ts = kc * a.L + wr0 + acc_row(v, g), col = nb2 * BD2 + nb * 32 + l32;
+            if (ts < a.out_T && col < a.out_cols)
+                Out[((long)bh * a.out_T + ts) * a.out_ld + col] = E::from_f32(acc[nb][v] * inv[v]);
         }
     if (MODE == MODE_DQ || MODE == MODE_DK) {
         const DT* W = reinterpret_cast<const DT*>(a.dotwith);
@@ -285,7 +287,12 @@ static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
         constexpr int OCC = (BD2 <= 128 && D1 <= 256) ? 2 : 1;
         // dQ / dK share the weighted matrix E through memory only where the contraction that forms it is wide
         constexpr int NOE = ((MODE == MODE_DQ || MODE == MODE_DK) && D1 <= TFLA_NOE_MAX_D1) ? 1 : 0;
-        hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT, NOE>), grid, dim3(64 * NW), 0, s, a);
+        // a padded problem stores its true part straight into the caller's tensor (the first half of a split
+        // contraction stores no output at all)
+        if (SPLIT != 1 && (a.out_T != a.T || a.out_ld != a.d2))
+            hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT, NOE, SPLIT != 1>), grid, dim3(64 * NW), 0, s, a);
+        else
+            hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT, NOE, 0>), grid, dim3(64 * NW), 0, s, a);
     } else {
         constexpr int BC = 32;   // two LDS stages must fit in 160 KB
         hipLaunchKernelGGL((tile_kernel<DT, D1, BD2, BC, NW, MODE, SPLIT>), grid, dim3(64 * NW), 0, s, a);

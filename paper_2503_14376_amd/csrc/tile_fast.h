@@ -31,7 +31,9 @@ static __device__ unsigned long long tfla_timeline[1 << 18];
 // accumulators, the second adds them to its own before the epilogue.
 // NOE: 1 = the dQ kernel does not store the weighted matrix E and the dK kernel recomputes it from dH and V
 // like every other mode (narrow contractions: E, L x L per chunk, is then more bytes than the operands it replaces).
-template <int D1, int BD2, int NW, int MODE, int OCC, int SPLIT = 0, int NOE = 0>
+// PADOUT: 1 = the kernel runs on a zero-padded copy of the problem and stores only the true steps and columns,
+// straight into the caller's tensor (TileArgs::out_T, out_ld, out_cols); 0 = whole blocks, nothing padded.
+template <int D1, int BD2, int NW, int MODE, int OCC, int SPLIT = 0, int NOE = 0, int PADOUT = 0>
 __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     using E = Elem<bf16_t>;
     using frag = E::frag;
@@ -531,13 +533,26 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             *reinterpret_cast<uint2*>(otile + l32 * ORB + (((4 * nb + j) ^ fsw) * 16) + 8 * g) = w;
         }
     {
-        char* obase = reinterpret_cast<char*>(a.Out) + ((tbase + wr0) * d2 + (long)nb2 * BD2) * 2;
         constexpr int RPI = 64 / OCPR;                   // tile rows covered by one 64-lane store
+        if constexpr (!PADOUT) {
+            char* obase = reinterpret_cast<char*>(a.Out) + ((tbase + wr0) * d2 + (long)nb2 * BD2) * 2;
 #pragma unroll
-        for (int q = 0; q < 32 / RPI; ++q) {
-            const int r = q * RPI + lane / OCPR, c = lane % OCPR;
-            const u32x4 w = *reinterpret_cast<const u32x4*>(otile + r * ORB + ((c ^ swz_mask<SWZ_K, OCPR>(r)) * 16));
-            *reinterpret_cast<u32x4*>(obase + (long)r * d2 * 2 + c * 16) = w;
+            for (int q = 0; q < 32 / RPI; ++q) {
+                const int r = q * RPI + lane / OCPR, c = lane % OCPR;
+                const u32x4 w = *reinterpret_cast<const u32x4*>(otile + r * ORB + ((c ^ swz_mask<SWZ_K, OCPR>(r)) * 16));
+                *reinterpret_cast<u32x4*>(obase + (long)r * d2 * 2 + c * 16) = w;
+            }
+        } else {
+            // straight into the caller's tensor: its own row count and row length, true steps and columns only
+            const int ts0 = kc * a.L + wr0;              // first step of this wave's rows within the sequence
+            char* obase = reinterpret_cast<char*>(a.Out) + (((long)bh * a.out_T + ts0) * a.out_ld + (long)nb2 * BD2) * 2;
+#pragma unroll
+            for (int q = 0; q < 32 / RPI; ++q) {
+                const int r = q * RPI + lane / OCPR, c = lane % OCPR;
+                const u32x4 w = *reinterpret_cast<const u32x4*>(otile + r * ORB + ((c ^ swz_mask<SWZ_K, OCPR>(r)) * 16));
+                if (ts0 + r < a.out_T && nb2 * BD2 + c * 8 < a.out_cols)
+                    *reinterpret_cast<u32x4*>(obase + (long)r * a.out_ld * 2 + c * 16) = w;
+            }
         }
     }
     if (MODE == MODE_DQ || MODE == MODE_DK) {
