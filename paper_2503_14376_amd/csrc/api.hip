@@ -83,6 +83,7 @@ inline size_t anchor_slots(const Dims& d) { const int G = anchor_G(d); return (s
 
 struct FwdWs {
     float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *nst, *Cfin, *pacc, *pnrm, *anc, *wrowB, *sQ;
+    float *wrow_lo, *ucol_lo, *wrowB_lo;   // fp32 kernels: rounding remainders of the exponents (NULL for bf16)
     void* stT;
     size_t bytes;
 };
@@ -90,10 +91,15 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
     Carver c(ws);
     FwdWs w;
     w.wrow = c.take<float>(d.BHT); w.ucol = c.take<float>(d.BHT); w.sH = c.take<float>(d.BHT);
-    w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
+    // (the fp32 kernels' gate pre-pass works in double: its scratch is twice the size)
+    const size_t gw = d.dtype == TFLA_BF16 ? 1 : 2;
+    w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(gw * 3 * d.BHT);
     w.wrowB = c.take<float>(d.BHT); w.sQ = c.take<float>(d.BHT);     // the backward pass's row weights (mLSTMexp)
     w.gbar = c.take<float>(d.BH * d.Nc);
-    w.csum = c.take<float>(2 * d.BH * d.Nc);
+    w.csum = c.take<float>(gw * 2 * d.BH * d.Nc);
+    w.wrow_lo = gw == 2 ? c.take<float>(d.BHT) : nullptr;
+    w.ucol_lo = gw == 2 ? c.take<float>(d.BHT) : nullptr;
+    w.wrowB_lo = gw == 2 ? c.take<float>(d.BHT) : nullptr;
     w.nst = c.take<float>(d.BH * d.Nc * d.dqk);
     w.Cfin = c.take<float>((size_t)d.BH * d.dqk * d.dhv);
     w.stT = c.take_bytes((size_t)d.BH * d.Nc * d.dqk * d.dhv * d.esz);
@@ -108,6 +114,7 @@ FwdWs carve_fwd(const Dims& d, void* ws) {
 
 struct BwdWs {
     float *wrow, *ucol, *sH, *aK, *gbar, *mout, *tmp, *csum, *wrowB, *sQ, *partQ, *partK, *cdot, *Cfinal, *anchor, *pacc, *ancC;
+    float *wrow_lo, *ucol_lo, *wrowB_lo;   // fp32 kernels: rounding remainders of the exponents (NULL for bf16)
     double* bsum;
     void *cN, *dcT, *dcN, *E, *E2;
     int nbQ, nbK;
@@ -117,9 +124,13 @@ BwdWs carve_bwd(const Dims& d, void* ws) {
     Carver c(ws);
     BwdWs w;
     w.wrow = c.take<float>(d.BHT); w.ucol = c.take<float>(d.BHT); w.sH = c.take<float>(d.BHT);
-    w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(3 * d.BHT);
+    const size_t gw = d.dtype == TFLA_BF16 ? 1 : 2;     // as in carve_fwd
+    w.aK = c.take<float>(d.BHT); w.mout = c.take<float>(d.BHT); w.tmp = c.take<float>(gw * 3 * d.BHT);
     w.gbar = c.take<float>(d.BH * d.Nc);
-    w.csum = c.take<float>(2 * d.BH * d.Nc);
+    w.csum = c.take<float>(gw * 2 * d.BH * d.Nc);
+    w.wrow_lo = gw == 2 ? c.take<float>(d.BHT) : nullptr;
+    w.ucol_lo = gw == 2 ? c.take<float>(d.BHT) : nullptr;
+    w.wrowB_lo = gw == 2 ? c.take<float>(d.BHT) : nullptr;
     w.bsum = c.take<double>(d.BH * ((d.T + 1023) / 1024));
     w.wrowB = c.take<float>(d.BHT); w.sQ = c.take<float>(d.BHT);
     w.nbQ = d.dqk / tile_bd2(d.dhv, d.dqk, d.dtype, MODE_DQ, d.L);
@@ -202,14 +213,15 @@ void prof_collect() {
 }
 
 int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float* m0, float* wrow, float* ucol,
-              float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, float* csum, float softcap,
-              int Tvalid, int dqk_true, hipStream_t s) {
+              float* sH, float* aK, float* gbar, float* mout, float* mfinal, float* tmp, float* csum, float* wrow_lo,
+              float* ucol_lo, float softcap, int Tvalid, int dqk_true, hipStream_t s) {
     GateArgs g;
     g.softcap = softcap; g.Tvalid = Tvalid;
     g.i_pre = i_pre; g.f_pre = f_pre; g.m0 = d.variant == TFLA_EXP ? m0 : nullptr;
     g.T = d.T; g.L = d.L; g.Nc = d.Nc; g.variant = d.variant;
     g.qscale = 1.0f / sqrtf((float)dqk_true);   // of the caller's head dimension, not of the padded one
     g.wrow = wrow; g.ucol = ucol; g.sH = sH; g.aK = aK; g.gbar = gbar; g.mout = mout; g.mfinal = mfinal; g.tmp = tmp; g.csum = csum;
+    g.wrow_lo = wrow_lo; g.ucol_lo = ucol_lo; g.precise = d.dtype == TFLA_BF16 ? 0 : 1;
     TFLA_LAUNCH(K_GATES, launch_gates(g, (int)d.BH, s));
     return TFLA_OK;
 }
@@ -235,7 +247,7 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
     // 1. gates, max states
     float* mout = (is_exp && m_out) ? m_out : w.mout;
-    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, softcap, Tvalid, dqk_true, s);
+    int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, mout, is_exp ? mn : nullptr, w.tmp, w.csum, w.wrow_lo, w.ucol_lo, softcap, Tvalid, dqk_true, s);
     if (st != TFLA_OK) return st;
 
     // 2. recurrent kernel: C_{k-1} (transposed, element type of q/k/v) and n_{k-1} for every chunk
@@ -255,6 +267,7 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.d1 = dqk; t.d2 = dhv;
     t.variant = variant; t.eps = eps; t.nstate = w.nst; t.mout = mout; t.nout = is_exp ? n_out : nullptr;
     t.wrowB_out = is_exp ? w.wrowB : nullptr; t.sQ_out = is_exp ? w.sQ : nullptr;
+    t.wrow_lo = w.wrow_lo; t.wcol_lo = w.ucol_lo; t.wrowB_lo_out = is_exp ? w.wrowB_lo : nullptr;
     t.dotwith = nullptr; t.dotpart = nullptr; t.E = nullptr;
     TFLA_LAUNCH(K_TILE_H, launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
 
@@ -310,25 +323,29 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     const float* sH = reuse ? fw.sH : w.sH;
     const float* aK = reuse ? fw.aK : w.aK;
     const float* gbar = reuse ? fw.gbar : w.gbar;
+    const float* wrow_lo = reuse ? fw.wrow_lo : w.wrow_lo;     // fp32 kernels only, NULL otherwise
+    const float* ucol_lo = reuse ? fw.ucol_lo : w.ucol_lo;
 
     // 1. gates as in the forward pass, then fold 1/h_denom into the backward weights
     if (!reuse) {
-        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, softcap, Tvalid, dqk_true, s);
+        int st = run_gates(d, i_pre, f_pre, m0, w.wrow, w.ucol, w.sH, w.aK, w.gbar, w.mout, nullptr, w.tmp, w.csum, w.wrow_lo, w.ucol_lo, softcap, Tvalid, dqk_true, s);
         if (st != TFLA_OK) return st;
     }
     // mLSTMsig has no denominator (the weights are the forward pass's own); for mLSTMexp the forward call has left
     // them in its workspace when it wrote n_out, otherwise they are formed here from n_out and m_out
     const float* wrowB = wrow;
+    const float* wrowB_lo = wrow_lo;
     const float* sQ = sH;
     if (is_exp) {
         if (reuse) {
-            wrowB = fw.wrowB; sQ = fw.sQ;
+            wrowB = fw.wrowB; sQ = fw.sQ; wrowB_lo = fw.wrowB_lo;
         } else {
             GateBwdPrepArgs p;
             p.wrow = wrow; p.sH = sH; p.n_out = n_out; p.m_out = m_out; p.wrowB = w.wrowB; p.sQ = w.sQ;
             p.n = d.BHT; p.variant = variant; p.eps = eps;
+            p.wrow_lo = wrow_lo; p.wrowB_lo = wrow_lo ? w.wrowB_lo : nullptr;
             TFLA_LAUNCH(K_BWD_PREP, launch_gate_bwd_prep(p, s));
-            wrowB = w.wrowB; sQ = w.sQ;
+            wrowB = w.wrowB; sQ = w.sQ; wrowB_lo = p.wrowB_lo;
         }
     }
 
@@ -363,15 +380,15 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     t.T = T; t.L = chunk; t.Nc = d.Nc; t.variant = variant; t.eps = eps;
     t.nstate = nullptr; t.mout = nullptr; t.nout = nullptr; t.E = w.E; t.E2 = w.E2; t.part_acc = w.pacc;
     // dV: rows = kv index j
-    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.out_T = Tvalid; t.out_ld = dhv_true; t.out_cols = dhv_true; t.wrow = ucol; t.wcol = wrowB; t.srow = aK; t.St = w.dcT;
+    t.X = k; t.Y = q; t.Z = dH; t.Out = dv; t.out_T = Tvalid; t.out_ld = dhv_true; t.out_cols = dhv_true; t.wrow_lo = ucol_lo; t.wcol_lo = wrowB_lo; t.wrowB_lo_out = nullptr; t.wrow = ucol; t.wcol = wrowB; t.srow = aK; t.St = w.dcT;
     t.d1 = dqk; t.d2 = dhv; t.dotwith = nullptr; t.dotpart = nullptr;
     TFLA_LAUNCH(K_TILE_DV, launch_tile_mode<MODE_DV>(t, (int)d.BH, dtype, s));
     // dQ: rows = query index i
-    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.out_ld = dqk_true; t.out_cols = dqk_true; t.wrow = wrowB; t.wcol = ucol; t.srow = sQ; t.St = cstates;
+    t.X = dH; t.Y = v; t.Z = k; t.Out = dq; t.out_ld = dqk_true; t.out_cols = dqk_true; t.wrow_lo = wrowB_lo; t.wcol_lo = ucol_lo; t.wrow = wrowB; t.wcol = ucol; t.srow = sQ; t.St = cstates;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = q; t.dotpart = w.partQ;
     TFLA_LAUNCH(K_TILE_DQ, launch_tile_mode<MODE_DQ>(t, (int)d.BH, dtype, s));
     // dK: rows = kv index j
-    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow = ucol; t.wcol = wrowB; t.srow = aK; t.St = tonly ? w.dcT : w.dcN;
+    t.X = v; t.Y = dH; t.Z = q; t.Out = dk; t.wrow_lo = ucol_lo; t.wcol_lo = wrowB_lo; t.wrow = ucol; t.wcol = wrowB; t.srow = aK; t.St = tonly ? w.dcT : w.dcN;
     t.d1 = dhv; t.d2 = dqk; t.dotwith = k; t.dotpart = w.partK;
     TFLA_LAUNCH(K_TILE_DK, launch_tile_mode<MODE_DK>(t, (int)d.BH, dtype, s));
 

@@ -21,26 +21,54 @@ __device__ __forceinline__ float sigmoid_neg(float x) {  // sigma(-x), no overfl
     return x >= 0.0f ? e / (1.0f + e) : 1.0f / (1.0f + e);
 }
 
-__device__ __forceinline__ float wave_excl_scan_add(float v, int lane) {
-    float x = v;
+// The pre-pass is written over an arithmetic type AT.  float serves the bf16 kernels.  The fp32 kernels get the
+// pre-pass in double (AT = double) and its two exponents as a (rounded, remainder) pair of floats each: the row and the
+// column term of a weight both have the size of the chunk's cumulative log forget gate and nearly cancel, so a single
+// float per term limits a weight to the fp32 spacing at that size (2.4e-4 at |sum f-bar| = 2560), while the sum of two
+// such pairs is exact to fp32 again.
+template <typename AT> __device__ __forceinline__ AT log_sigmoid_t(AT x);
+template <> __device__ __forceinline__ float log_sigmoid_t<float>(float x) { return log_sigmoid(x); }
+template <> __device__ __forceinline__ double log_sigmoid_t<double>(double x) { return fmin(x, 0.0) - log1p(exp(-fabs(x))); }
+template <typename AT> __device__ __forceinline__ AT soft_cap_t(AT x, float c);
+template <> __device__ __forceinline__ float soft_cap_t<float>(float x, float c) { return soft_cap(x, c); }
+template <> __device__ __forceinline__ double soft_cap_t<double>(double x, float c) { return c > 0.0f ? (double)c * tanh(x / (double)c) : x; }
+template <typename AT> __device__ __forceinline__ AT max_t(AT x, AT y);
+template <> __device__ __forceinline__ float max_t<float>(float x, float y) { return fmaxf(x, y); }
+template <> __device__ __forceinline__ double max_t<double>(double x, double y) { return fmax(x, y); }
+template <typename AT> __device__ __forceinline__ AT exp_t(AT x);
+template <> __device__ __forceinline__ float exp_t<float>(float x) { return expf(x); }
+template <> __device__ __forceinline__ double exp_t<double>(double x) { return exp(x); }
+
+template <typename AT> __device__ __forceinline__ AT wave_excl_scan_add(AT v, int lane) {
+    AT x = v;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { const float y = __shfl_up(x, o, 64); if (lane >= o) x += y; }
-    const float p = __shfl_up(x, 1, 64);
-    return lane == 0 ? 0.0f : p;
+    for (int o = 1; o < 64; o <<= 1) { const AT y = __shfl_up(x, o, 64); if (lane >= o) x += y; }
+    const AT p = __shfl_up(x, 1, 64);
+    return lane == 0 ? (AT)0 : p;
 }
-__device__ __forceinline__ float wave_excl_rscan_add(float v, int lane) {
-    float x = v;
+template <typename AT> __device__ __forceinline__ AT wave_excl_rscan_add(AT v, int lane) {
+    AT x = v;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { const float y = __shfl_down(x, o, 64); if (lane + o < 64) x += y; }
-    const float p = __shfl_down(x, 1, 64);
-    return lane == 63 ? 0.0f : p;
+    for (int o = 1; o < 64; o <<= 1) { const AT y = __shfl_down(x, o, 64); if (lane + o < 64) x += y; }
+    const AT p = __shfl_down(x, 1, 64);
+    return lane == 63 ? (AT)0 : p;
 }
-__device__ __forceinline__ float wave_excl_scan_max(float v, int lane) {
-    float x = v;
+template <typename AT> __device__ __forceinline__ AT wave_excl_scan_max(AT v, int lane) {
+    AT x = v;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { const float y = __shfl_up(x, o, 64); if (lane >= o) x = fmaxf(x, y); }
-    const float p = __shfl_up(x, 1, 64);
-    return lane == 0 ? -INFINITY : p;
+    for (int o = 1; o < 64; o <<= 1) { const AT y = __shfl_up(x, o, 64); if (lane >= o) x = max_t<AT>(x, y); }
+    const AT p = __shfl_up(x, 1, 64);
+    return lane == 0 ? (AT)-INFINITY : p;
+}
+template <typename AT> __device__ __forceinline__ AT wave_sum_t(AT x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+template <typename AT> __device__ __forceinline__ AT wave_max_t(AT x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = max_t<AT>(x, __shfl_xor(x, o, 64));
+    return x;
 }
 
 // The gate pre-pass runs as two kernels, each with one wavefront per chunk (four chunks per
@@ -61,7 +89,8 @@ static constexpr int GATE_WAVES = 4;
 
 // EC > 0: the lane's E <= EC steps keep their log gates in registers (one evaluation of the logarithms per
 // step instead of one per pass); EC = 0: any E, the log gates are evaluated again in every pass.
-template <int EC>
+// tmp and csum hold values of type AT.
+template <int EC, typename AT>
 __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a) {
     const int bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kc = blockIdx.x * GATE_WAVES + wave;
@@ -69,108 +98,115 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_chunk_kernel(GateArgs a
     const int E = a.L / 64;
     const bool is_exp = a.variant == 0;
     const long row = (long)bh * a.T;
-    float* tb = a.tmp + (long)bh * 3 * a.T;
-    float* tc = tb + a.T;
-    float* ta = tc + a.T;
+    AT* tb = reinterpret_cast<AT*>(a.tmp) + (long)bh * 3 * a.T;
+    AT* tc = tb + a.T;
+    AT* ta = tc + a.T;
+    AT* csum = reinterpret_cast<AT*>(a.csum);
+    const AT log2e = (AT)1.4426950408889634;
     const long t0 = (long)kc * a.L + (long)lane * E;
     // log gates of step t; the padding steps of a sequence that does not fill its last chunk keep the
     // state as it is (log forget gate 0) and add nothing (log input gate far below every other)
-    auto fbar_at = [&](long t) { return t < a.Tvalid ? log_sigmoid(soft_cap(a.f_pre[row + t], a.softcap)) : 0.0f; };
+    auto fbar_at = [&](long t) { return t < a.Tvalid ? log_sigmoid_t<AT>(soft_cap_t<AT>((AT)a.f_pre[row + t], a.softcap)) : (AT)0; };
     auto ibar_at = [&](long t) {
-        if (t >= a.Tvalid) return -1.0e30f;
-        const float ip = soft_cap(a.i_pre[row + t], a.softcap);
-        return is_exp ? ip : log_sigmoid(ip);
+        if (t >= a.Tvalid) return (AT)-1.0e30f;
+        const AT ip = soft_cap_t<AT>((AT)a.i_pre[row + t], a.softcap);
+        return is_exp ? ip : log_sigmoid_t<AT>(ip);
     };
     constexpr int NC = EC > 0 ? EC : 1;
-    float fbv[NC], ibv[NC];
+    AT fbv[NC], ibv[NC];
     if constexpr (EC > 0) {
 #pragma unroll
         for (int e = 0; e < EC; ++e) {
-            fbv[e] = 0.0f; ibv[e] = 0.0f;
+            fbv[e] = (AT)0; ibv[e] = (AT)0;
             if (e < E) { fbv[e] = fbar_at(t0 + e); ibv[e] = ibar_at(t0 + e); }
         }
     }
     auto fbar = [&](int e) { if constexpr (EC > 0) return fbv[e]; else return fbar_at(t0 + e); };
     auto ibar = [&](int e) { if constexpr (EC > 0) return ibv[e]; else return ibar_at(t0 + e); };
     const int EB = EC > 0 ? EC : E;                 // loop bound (compile-time when the gates are cached)
-    float fsum = 0.0f;
+    AT fsum = (AT)0;
 #pragma unroll
     for (int e = 0; e < EB; ++e)
         if (e < E) fsum += fbar(e);
-    const float off = wave_excl_scan_add(fsum, lane);
-    const float roff = wave_excl_rscan_add(fsum, lane);
+    const AT off = wave_excl_scan_add<AT>(fsum, lane);
+    const AT roff = wave_excl_rscan_add<AT>(fsum, lane);
     // forward pass: b, u = i-bar - b, running max of u
-    float b = off, cmx = -INFINITY;
+    AT b = off, cmx = (AT)-INFINITY;
 #pragma unroll
     for (int e = 0; e < EB; ++e)
         if (e < E) {
             b += fbar(e);
-            cmx = fmaxf(cmx, ibar(e) - b);
+            cmx = max_t<AT>(cmx, ibar(e) - b);
         }
-    const float cmoff = wave_excl_scan_max(cmx, lane);
+    const AT cmoff = wave_excl_scan_max<AT>(cmx, lane);
     b = off; cmx = cmoff;
 #pragma unroll
     for (int e = 0; e < EB; ++e)
         if (e < E) {
             b += fbar(e);
-            const float u = ibar(e) - b;
-            cmx = fmaxf(cmx, u);
+            const AT u = ibar(e) - b;
+            cmx = max_t<AT>(cmx, u);
             tb[t0 + e] = b;
             tc[t0 + e] = cmx;
-            a.ucol[row + t0 + e] = u * LOG2E;
+            const AT ul = u * log2e;
+            const float uh = (float)ul;
+            a.ucol[row + t0 + e] = uh;
+            if (a.ucol_lo) a.ucol_lo[row + t0 + e] = (float)(ul - (AT)uh);
         }
     // reverse pass: a_j = sum_{s>j} f-bar_s + i-bar_j
-    float run = roff, amax = -INFINITY;
+    AT run = roff, amax = (AT)-INFINITY;
 #pragma unroll
     for (int e = EB - 1; e >= 0; --e)
         if (e < E) {
-            const float av = run + ibar(e);
+            const AT av = run + ibar(e);
             ta[t0 + e] = av;
-            amax = fmaxf(amax, av);
+            amax = max_t<AT>(amax, av);
             run += fbar(e);
         }
-    amax = wave_max(amax);
-    const float gsum = wave_sum(fsum);
+    amax = wave_max_t<AT>(amax);
+    const AT gsum = wave_sum_t<AT>(fsum);
     if (lane == 0) {
-        a.csum[((long)bh * 2 + 0) * a.Nc + kc] = gsum;
-        a.csum[((long)bh * 2 + 1) * a.Nc + kc] = amax;
+        csum[((long)bh * 2 + 0) * a.Nc + kc] = gsum;
+        csum[((long)bh * 2 + 1) * a.Nc + kc] = amax;
     }
 }
 
+template <typename AT>
 __global__ void __launch_bounds__(GATE_WAVES * 64) gates_step_kernel(GateArgs a) {
-    extern __shared__ float cm[];   // [Nc + 1]: m before chunk k
+    extern __shared__ double cm_raw[];   // [Nc + 1] values of type AT: m before chunk k
+    AT* cm = reinterpret_cast<AT*>(cm_raw);
     const int bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool is_exp = a.variant == 0;
-    const float* cg = a.csum + ((long)bh * 2 + 0) * a.Nc;
-    const float* camax = a.csum + ((long)bh * 2 + 1) * a.Nc;
+    const AT* cg = reinterpret_cast<const AT*>(a.csum) + ((long)bh * 2 + 0) * a.Nc;
+    const AT* camax = reinterpret_cast<const AT*>(a.csum) + ((long)bh * 2 + 1) * a.Nc;
     if (wave == 0) {
         // lane l composes the maps of its segment of chunks, a wavefront scan composes the segments,
         // then every lane walks its segment again from its incoming m
         const int seg = (a.Nc + 63) / 64;
         const int k0 = lane * seg, k1 = min(a.Nc, k0 + seg);
-        float G = 0.0f, C = -INFINITY;
-        for (int k = k0; k < k1; ++k) { C = fmaxf(C + cg[k], camax[k]); G += cg[k]; }
+        AT G = (AT)0, C = (AT)-INFINITY;
+        for (int k = k0; k < k1; ++k) { C = max_t<AT>(C + cg[k], camax[k]); G += cg[k]; }
         // inclusive scan of the composed maps over the lanes
-        float Gs = G, Cs = C;
+        AT Gs = G, Cs = C;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
-            const float Gp = __shfl_up(Gs, o, 64), Cp = __shfl_up(Cs, o, 64);
-            if (lane >= o) { Cs = fmaxf(Cp + Gs, Cs); Gs = Gp + Gs; }
+            const AT Gp = __shfl_up(Gs, o, 64), Cp = __shfl_up(Cs, o, 64);
+            if (lane >= o) { Cs = max_t<AT>(Cp + Gs, Cs); Gs = Gp + Gs; }
         }
         // exclusive: the map of all chunks before this lane's segment, applied to m0
-        const float Ge = __shfl_up(Gs, 1, 64), Ce = __shfl_up(Cs, 1, 64);
-        const float m_init = (is_exp && a.m0) ? a.m0[bh] : 0.0f;
-        float m = lane == 0 ? m_init : fmaxf(m_init + Ge, Ce);
-        if (!is_exp) m = 0.0f;
+        const AT Ge = __shfl_up(Gs, 1, 64), Ce = __shfl_up(Cs, 1, 64);
+        const AT m_init = (is_exp && a.m0) ? (AT)a.m0[bh] : (AT)0;
+        AT m = lane == 0 ? m_init : max_t<AT>(m_init + Ge, Ce);
+        if (!is_exp) m = (AT)0;
         for (int k = k0; k < k1; ++k) {
             cm[k] = m;
-            const float mn = is_exp ? fmaxf(cg[k] + m, camax[k]) : 0.0f;
-            if (blockIdx.x == 0) a.gbar[(long)bh * a.Nc + k] = expf(cg[k] + m - mn);
+            const AT mn = is_exp ? max_t<AT>(cg[k] + m, camax[k]) : (AT)0;
+            if (blockIdx.x == 0) a.gbar[(long)bh * a.Nc + k] = (float)exp_t<AT>(cg[k] + m - mn);
             m = mn;
         }
         if (k1 == a.Nc && k0 < k1) {
             cm[a.Nc] = m;
-            if (blockIdx.x == 0 && a.mfinal) a.mfinal[bh] = m;
+            if (blockIdx.x == 0 && a.mfinal) a.mfinal[bh] = (float)m;
         }
     }
     __syncthreads();
@@ -178,43 +214,51 @@ __global__ void __launch_bounds__(GATE_WAVES * 64) gates_step_kernel(GateArgs a)
     if (kc >= a.Nc) return;
     const int E = a.L / 64;
     const long row = (long)bh * a.T;
-    const float* tb = a.tmp + (long)bh * 3 * a.T;
-    const float* tc = tb + a.T;
-    const float* ta = tc + a.T;
-    const float lq = log2f(a.qscale);
+    const AT* tb = reinterpret_cast<const AT*>(a.tmp) + (long)bh * 3 * a.T;
+    const AT* tc = tb + a.T;
+    const AT* ta = tc + a.T;
+    const AT log2e = (AT)1.4426950408889634;
+    const AT lq = (AT)log2f(a.qscale);
     const long t0 = (long)kc * a.L + (long)lane * E;
-    const float mprev = cm[kc], mk = cm[kc + 1];
+    const AT mprev = cm[kc], mk = cm[kc + 1];
     for (int e = 0; e < E; ++e) {
-        const float b = tb[t0 + e], cmx = tc[t0 + e], av = ta[t0 + e];
-        float wr, sh, mo;
+        const AT b = tb[t0 + e], cmx = tc[t0 + e], av = ta[t0 + e];
+        AT wr, sh, mo;
         if (is_exp) {
-            const float M = fmaxf(mprev, cmx);
-            wr = -M * LOG2E + lq;
-            sh = expf(mprev - M) * a.qscale;
+            const AT M = max_t<AT>(mprev, cmx);
+            wr = -M * log2e + lq;
+            sh = exp_t<AT>(mprev - M) * (AT)a.qscale;
             mo = b + M;
         } else {
-            wr = b * LOG2E + lq;
-            sh = expf(b) * a.qscale;
-            mo = 0.0f;
+            wr = b * log2e + lq;
+            sh = exp_t<AT>(b) * (AT)a.qscale;
+            mo = (AT)0;
         }
-        a.wrow[row + t0 + e] = wr;
-        a.sH[row + t0 + e] = sh;
-        a.aK[row + t0 + e] = expf(av - mk);
-        a.mout[row + t0 + e] = mo;
+        const float wh = (float)wr;
+        a.wrow[row + t0 + e] = wh;
+        if (a.wrow_lo) a.wrow_lo[row + t0 + e] = (float)(wr - (AT)wh);
+        a.sH[row + t0 + e] = (float)sh;
+        a.aK[row + t0 + e] = (float)exp_t<AT>(av - mk);
+        a.mout[row + t0 + e] = (float)mo;
     }
 }
 
-hipError_t launch_gates(const GateArgs& a, int BH, hipStream_t s) {
+template <typename AT> static hipError_t launch_gates_t(const GateArgs& a, int BH, hipStream_t s) {
     const dim3 grid((a.Nc + GATE_WAVES - 1) / GATE_WAVES, BH);
     // the log gates of a lane's steps stay in registers for every chunk size the library accepts (L <= 2048)
-    if (a.L / 64 <= 8) hipLaunchKernelGGL(gates_chunk_kernel<8>, grid, dim3(GATE_WAVES * 64), 0, s, a);
-    else if (a.L / 64 <= 16) hipLaunchKernelGGL(gates_chunk_kernel<16>, grid, dim3(GATE_WAVES * 64), 0, s, a);
-    else if (a.L / 64 <= 32) hipLaunchKernelGGL(gates_chunk_kernel<32>, grid, dim3(GATE_WAVES * 64), 0, s, a);
-    else hipLaunchKernelGGL(gates_chunk_kernel<0>, grid, dim3(GATE_WAVES * 64), 0, s, a);
+    if (a.L / 64 <= 8) hipLaunchKernelGGL((gates_chunk_kernel<8, AT>), grid, dim3(GATE_WAVES * 64), 0, s, a);
+    else if (a.L / 64 <= 16) hipLaunchKernelGGL((gates_chunk_kernel<16, AT>), grid, dim3(GATE_WAVES * 64), 0, s, a);
+    else if (a.L / 64 <= 32) hipLaunchKernelGGL((gates_chunk_kernel<32, AT>), grid, dim3(GATE_WAVES * 64), 0, s, a);
+    else hipLaunchKernelGGL((gates_chunk_kernel<0, AT>), grid, dim3(GATE_WAVES * 64), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gates_step_kernel, grid, dim3(GATE_WAVES * 64), sizeof(float) * (size_t)(a.Nc + 1), s, a);
+    hipLaunchKernelGGL(gates_step_kernel<AT>, grid, dim3(GATE_WAVES * 64), sizeof(AT) * (size_t)(a.Nc + 1), s, a);
     return hipGetLastError();
+}
+
+// a.precise: the fp32 kernels' pre-pass (double arithmetic, two-float exponents; tmp and csum then hold doubles)
+hipError_t launch_gates(const GateArgs& a, int BH, hipStream_t s) {
+    return a.precise ? launch_gates_t<double>(a, BH, s) : launch_gates_t<float>(a, BH, s);
 }
 
 // Backward preparation: fold delta H~ = delta H / h_denom (App. B.3) into the weights.
@@ -223,7 +267,15 @@ __global__ void gate_bwd_prep_kernel(GateBwdPrepArgs a) {
     if (i >= a.n) return;
     float den = 1.0f;
     if (a.variant == 0) den = fmaxf(fabsf(a.n_out[i]), expf(-a.m_out[i])) + a.eps;
-    a.wrowB[i] = a.wrow[i] - log2f(den);
+    if (a.wrowB_lo) {
+        // fp32 kernels: the difference to double accuracy, as a (rounded, remainder) pair
+        const double w = (double)a.wrow[i] + (double)a.wrow_lo[i] - log2((double)den);
+        const float wh = (float)w;
+        a.wrowB[i] = wh;
+        a.wrowB_lo[i] = (float)(w - (double)wh);
+    } else {
+        a.wrowB[i] = a.wrow[i] - log2f(den);
+    }
     a.sQ[i] = a.sH[i] / den;
 }
 hipError_t launch_gate_bwd_prep(const GateBwdPrepArgs& a, hipStream_t s) {

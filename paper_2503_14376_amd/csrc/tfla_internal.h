@@ -23,7 +23,10 @@ struct GateArgs {
     float* gbar;          // (BH, Nc) g-bar_k
     float* mout;          // combined max state m_t of every step
     float* mfinal;        // (BH) m after the last chunk, or NULL
-    float* tmp;           // (BH, 3, T) scratch
+    float* tmp;           // (BH, 3, T) scratch (values of the pre-pass's arithmetic type: doubles when `precise`)
+    // fp32 kernels: pre-pass in double, and the rounding remainders of the two exponents (wrow + wrow_lo and
+    // ucol + ucol_lo are the exponents to double accuracy); csum then holds doubles as well.  NULL / 0 otherwise.
+    float* wrow_lo; float* ucol_lo; int precise;
     float* csum;          // (BH, 2, Nc) scratch: per-chunk sum of f-bar and max of a
 };
 hipError_t launch_gates(const GateArgs& a, int BH, hipStream_t s);
@@ -32,6 +35,7 @@ struct GateBwdPrepArgs {
     const float* wrow; const float* sH; const float* n_out; const float* m_out;
     float* wrowB; float* sQ;
     long n; int variant; float eps;
+    const float* wrow_lo; float* wrowB_lo;   // fp32 kernels: remainders of wrow / wrowB, or NULL
 };
 hipError_t launch_gate_bwd_prep(const GateBwdPrepArgs& a, hipStream_t s);
 
@@ -194,6 +198,9 @@ struct TileArgs {
     // problem: only steps t < out_T and columns < out_cols are stored, rows are out_ld elements apart
     // (out_T = T, out_ld = out_cols = d2 when nothing is padded).  out_cols is a multiple of 8.
     int out_T, out_ld, out_cols;
+    // fp32 kernels: rounding remainders of the row and column exponents (the weight is exp2 of the sum of all four),
+    // and where MODE_H leaves the remainder that belongs to wrowB_out; NULL = none
+    const float* wrow_lo; const float* wcol_lo; float* wrowB_lo_out;
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
 // d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16

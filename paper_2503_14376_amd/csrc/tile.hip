@@ -43,6 +43,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     __shared__ __attribute__((aligned(16))) DT ldsY[2][BC * YS];
     __shared__ __attribute__((aligned(16))) DT ldsZ[2][BD2 * ZS];
     __shared__ float ldsW[2][BC];
+    __shared__ float ldsWl[2][BC];     // rounding remainders of the column exponents (zeros when there are none)
     __shared__ float ldsR[NW * 32];
     __shared__ float ldsN[(MODE == MODE_H) ? D1 : 1];
 
@@ -69,6 +70,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     const DT* Z = reinterpret_cast<const DT*>(a.Z) + tbase * d2 + (long)nb2 * BD2;
     const DT* St = reinterpret_cast<const DT*>(a.St) + (((long)bh * a.Nc + kc) * d2 + (long)nb2 * BD2) * ld1;
     const float* wcol = a.wcol + tbase;
+    const float* wcol_lo = a.wcol_lo ? a.wcol_lo + tbase : nullptr;
 
     // X fragments of the wavefront's 32 rows (lane: row l32, k-group g)
     frag xf[KS1];
@@ -94,7 +96,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
     RowsPrefetch<DT, BD2, BC, NT> ps;          // state chunk  [BD2][BC]
     RowsPrefetch<DT, BC, D1, NT> py;           // Y tile       [BC][D1]
     TrPrefetch<DT, BC, BD2, NT, true> pz;      // Z tile       [BC][BD2] -> [BD2][BC]
-    float pw = 0.0f;
+    float pw = 0.0f, pwl = 0.0f;
     int buf = 0;
 
     // ---------------- inter-chunk part: acc = X_r St, BC columns of d1 per stage
@@ -108,7 +110,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
         } else {
             py.load(Y + (long)ct_lo * BC * ld1, ld1, tid);
             pz.load(Z + (long)ct_lo * BC * d2, d2, tid);
-            if (tid < BC) pw = wcol[ct_lo * BC + tid];
+            if (tid < BC) { pw = wcol[ct_lo * BC + tid]; pwl = wcol_lo ? wcol_lo[ct_lo * BC + tid] : 0.0f; }
         }
         const DT* zb = ldsZ[buf];
 #pragma unroll
@@ -121,7 +123,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
         } else {
             py.store(ldsY[buf ^ 1], YS, tid);
             pz.template store<false>(ldsZ[buf ^ 1], ZS, nullptr, tid);
-            if (tid < BC) ldsW[buf ^ 1][tid] = pw;
+            if (tid < BC) { ldsW[buf ^ 1][tid] = pw; ldsWl[buf ^ 1][tid] = pwl; }
         }
         __syncthreads();
         buf ^= 1;
@@ -152,6 +154,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 
     // ---------------- intra-chunk part
     const float wr = a.wrow[tbase + wr0 + l32];
+    const float wrl = a.wrow_lo ? a.wrow_lo[tbase + wr0 + l32] : 0.0f;
     float rowsum = 0.0f;
     for (int ct = ct_lo; ct < ct_hi; ++ct) {
         const int c0 = ct * BC;
@@ -159,11 +162,12 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
         if (more) {
             py.load(Y + (long)(c0 + BC) * ld1, ld1, tid);
             pz.load(Z + (long)(c0 + BC) * d2, d2, tid);
-            if (tid < BC) pw = wcol[c0 + BC + tid];
+            if (tid < BC) { pw = wcol[c0 + BC + tid]; pwl = wcol_lo ? wcol_lo[c0 + BC + tid] : 0.0f; }
         }
         const DT* yb = ldsY[buf];
         const DT* zb = ldsZ[buf];
         const float* wb = ldsW[buf];
+        const float* wbl = ldsWl[buf];
 #pragma unroll
         for (int st = 0; st < BC / 32; ++st) {
             const int cs = c0 + 32 * st;
@@ -179,7 +183,8 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int cl = acc_row(v, g);
-                float w = fast_exp2(wr + wb[32 * st + cl]);
+                // (rounded parts first: they nearly cancel, and their sum is exact in fp32)
+                float w = fast_exp2((wr + wb[32 * st + cl]) + (wrl + wbl[32 * st + cl]));
                 if (diag) {
                     const bool keep = UPPER ? (cs + cl >= wr0 + l32) : (cs + cl <= wr0 + l32);
                     w = keep ? w : 0.0f;
@@ -198,7 +203,7 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
         if (more) {
             py.store(ldsY[buf ^ 1], YS, tid);
             pz.template store<false>(ldsZ[buf ^ 1], ZS, nullptr, tid);
-            if (tid < BC) ldsW[buf ^ 1][tid] = pw;
+            if (tid < BC) { ldsW[buf ^ 1][tid] = pw; ldsWl[buf ^ 1][tid] = pwl; }
         }
         __syncthreads();
         buf ^= 1;
@@ -244,7 +249,14 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
                 ldsR[wave * 32 + l32] = 1.0f / den;
                 if (a.nout && nb2 == 0) a.nout[t] = nrm;
                 if (a.wrowB_out && nb2 == 0) {
-                    a.wrowB_out[t] = a.wrow[t] - log2f(den);
+                    if (a.wrowB_lo_out) {
+                        const double w = (double)wr + (double)wrl - log2((double)den);
+                        const float wh = (float)w;
+                        a.wrowB_out[t] = wh;
+                        a.wrowB_lo_out[t] = (float)(w - (double)wh);
+                    } else {
+                        a.wrowB_out[t] = a.wrow[t] - log2f(den);
+                    }
                     a.sQ_out[t] = a.srow[t] / den;
                 }
             }
