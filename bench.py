@@ -63,7 +63,7 @@ def algorithmic_bytes(w: wl.Workload, es: int):
         # fp32 copies of the state at the block boundaries of the anchored forget-gate gradient scan (every fourth
         # chunk, blocks of at most 2048 steps): the forward launch writes them, the reversed launch reads them
         nc = w.T // w.chunk
-        G = 1 if max(w.dqk, w.dhv) > 512 else (4 if 4 * w.chunk <= 2048 else max(1, 2048 // w.chunk))
+        G = 2 if max(w.dqk, w.dhv) > 512 else (4 if 4 * w.chunk <= 2048 else max(1, 2048 // w.chunk))
         rec += w.B * w.NH * max(0, (nc + G - 1) // G - 1) * w.dqk * w.dhv * 4
     # the weighted intra-chunk matrix E, lower triangle: where the contraction over d_hv is wider than 256 columns
     # (bf16 path) dQ writes it and dK reads it instead of dH; narrower heads recompute it in dK

@@ -65,11 +65,11 @@ hipError_t launch_unpad_rows(const void* in, void* out, long BH, int T, int Tp, 
 hipError_t launch_pad_scalar(const float* in, float* out, long BH, int T, int Tp, float fill, hipStream_t s);
 hipError_t launch_unpad_scalar(const float* in, float* out, long BH, int T, int Tp, hipStream_t s);
 hipError_t launch_state_dot(const float* A, const float* Bm, float* out, long per, int BH, hipStream_t s);
-// Chunks per block of the anchored forget-gate gradient scan: four (a block has at most 2048 steps); one for heads
+// Chunks per block of the anchored forget-gate gradient scan: four (a block has at most 2048 steps); two for heads
 // wider than 512, where a row's dot products run over so many terms that the noise of a few chunks already shows
 // (behind a norm layer the forget-gate gradient is what survives of an almost complete cancellation).
 inline int anchor_chunks(int L, int dwide) {
-    if (dwide > 512) return 1;
+    if (dwide > 512) return 2;
     return 4 * L <= 2048 ? 4 : (2048 / L > 0 ? 2048 / L : 1);
 }
 
