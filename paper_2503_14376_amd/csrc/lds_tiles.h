@@ -69,6 +69,27 @@ __device__ __forceinline__ void dma16_free(const void* gbase_uniform, uint32_t v
                  :: "s"(la), "v"(voff), "s"(gu) : "m0");
 }
 
+// The two loads above with the non-temporal hint: for operands that exactly one workgroup of the launch reads,
+// so that they do not displace what several workgroups share from the caches.
+__device__ __forceinline__ void dma16_nt(const void* gbase_uniform, uint32_t voff, uint32_t lds_uniform) {
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_uniform);
+    const uint64_t gb = (uint64_t)(uintptr_t)gbase_uniform;
+    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
+    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
+    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :: "s"(la), "v"(voff), "s"(gu) : "memory", "m0");
+}
+__device__ __forceinline__ void dma16_free_nt(const void* gbase_uniform, uint32_t voff, uint32_t lds_uniform) {
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_uniform);
+    const uint64_t gb = (uint64_t)(uintptr_t)gbase_uniform;
+    const uint32_t glo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb);
+    const uint32_t ghi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32));
+    const uint64_t gu = (uint64_t)glo | ((uint64_t)ghi << 32);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :: "s"(la), "v"(voff), "s"(gu) : "m0");
+}
+
 // Same for 64 x 4 bytes: lane l copies one dword to LDS address lds_uniform + 4 * l.
 __device__ __forceinline__ void dma4(const void* gbase_uniform, uint32_t voff, uint32_t lds_uniform) {
     const uint32_t la = __builtin_amdgcn_readfirstlane(lds_uniform);
@@ -119,17 +140,26 @@ template <int ROWS, int COLS, int NT, int KIND> struct DmaTile {
         }
     }
     // gtile: wave-uniform address of the tile's first element; lds: LDS address of the tile
+    // ONCE: with the non-temporal hint (a tile that no other workgroup reads)
+    template <bool ONCE = false>
     __device__ __forceinline__ void issue(const bf16_t* gtile, uint32_t lds, int tid) const {
         const int wave = tid >> 6;
 #pragma unroll
-        for (int j = 0; j < N; ++j) dma16(gtile, goff[j], lds + (wave + j * NWV) * 1024);
+        for (int j = 0; j < N; ++j) {
+            if constexpr (ONCE) dma16_nt(gtile, goff[j], lds + (wave + j * NWV) * 1024);
+            else dma16(gtile, goff[j], lds + (wave + j * NWV) * 1024);
+        }
     }
     // the loads j = part, part + nparts, ... only (part, nparts compile-time in the callers)
+    template <bool ONCE = false>
     __device__ __forceinline__ void issue_part(const bf16_t* gtile, uint32_t lds, int tid, int part, int nparts) const {
         const int wave = tid >> 6;
 #pragma unroll
         for (int j = 0; j < N; ++j)
-            if (j % nparts == part) dma16_free(gtile, goff[j], lds + (wave + j * NWV) * 1024);
+            if (j % nparts == part) {
+                if constexpr (ONCE) dma16_free_nt(gtile, goff[j], lds + (wave + j * NWV) * 1024);
+                else dma16_free(gtile, goff[j], lds + (wave + j * NWV) * 1024);
+            }
     }
 };
 

@@ -16,7 +16,8 @@ constexpr int NORM_RPB = 128;   // rows per workgroup of the backward kernel (32
 template <typename DT> struct Row8;
 template <> struct Row8<bf16_t> {
     static __device__ __forceinline__ void load(const void* base, long idx, float (&x)[8]) {
-        const u32x4 w = *reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16_t*>(base) + idx);
+        // every row is read once per launch: non-temporal, so that the stream does not displace other data from the caches
+        const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16_t*>(base) + idx));
 #pragma unroll
         for (int e = 0; e < 4; ++e) { x[2 * e] = bf16_lo_to_f32(w[e]); x[2 * e + 1] = bf16_hi_to_f32(w[e]); }
     }
@@ -25,6 +26,13 @@ template <> struct Row8<bf16_t> {
 #pragma unroll
         for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
         *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(base) + idx) = w;
+    }
+    // for results that the next kernels do not read
+    static __device__ __forceinline__ void store_stream(void* base, long idx, const float (&x)[8]) {
+        u32x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(base) + idx));
     }
 };
 template <> struct Row8<float> {
@@ -38,6 +46,7 @@ template <> struct Row8<float> {
         p[0] = make_float4(x[0], x[1], x[2], x[3]);
         p[1] = make_float4(x[4], x[5], x[6], x[7]);
     }
+    static __device__ __forceinline__ void store_stream(void* base, long idx, const float (&x)[8]) { store(base, idx, x); }
 };
 
 __device__ __forceinline__ void load8f(const float* p, float (&x)[8]) {
@@ -115,7 +124,7 @@ __global__ void __launch_bounds__(256) norm_gate_fwd_kernel(NormArgs a) {
             const float n = r.x[j][e] * rstd * g[e] + be[e];
             y[e] = a.o_pre ? n * sigmoidf_(o[e]) : n;
         }
-        Row8<DT>::store(a.y, row * d + c, y);
+        Row8<DT>::store_stream(a.y, row * d + c, y);
     }
 }
 
@@ -175,7 +184,7 @@ __global__ void __launch_bounds__(256) norm_gate_bwd_kernel(NormBwdArgs a) {
                 s1 += dx[j][e];
                 s2 += dx[j][e] * xh;
             }
-            if (a.o_pre && a.do_pre) Row8<DT>::store(a.do_pre, row * d + c, dop);
+            if (a.o_pre && a.do_pre) Row8<DT>::store_stream(a.do_pre, row * d + c, dop);
         }
         s1 = a.kind == 1 ? wave_sum(s1) / (float)d : 0.0f;
         s2 = wave_sum(s2) / (float)d;

@@ -12,6 +12,7 @@
 #include "lds_tiles.h"
 #include "tfla_internal.h"
 
+
 namespace tfla {
 
 // Development aid, compiled only with -DTFLA_TIMELINE: wave 0 of every workgroup records the
@@ -127,14 +128,18 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     auto issue = [&](int item) {
         const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
         if (item < NXS) {
-            dxs.issue(Xb + item * BXS, st, tid);
+            // the workgroup's own rows: no other workgroup reads them when its block covers all output columns
+            if (gx == 1) dxs.template issue<true>(Xb + item * BXS, st, tid);
+            else dxs.issue(Xb + item * BXS, st, tid);
         } else if (item < NPRE) {
             const int sl = item - NXS;
-            ds.issue(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid);
+            // (state slices of the dQ / dK kernels carry the hint too: measured, -3 us on dQ)
+            ds.template issue<STT>(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid);
         } else {
             const int ct = ct_lo + item - NPRE;
             if (ELITE) {
-                dy.issue(Eb + (long)ct * BC * a.L, st, tid);
+                // (E of this workgroup's rows: read by this workgroup only)
+                dy.template issue<true>(Eb + (long)ct * BC * a.L, st, tid);
                 dz.issue(Z + (long)ct * BC * d2, st + YB, tid);
             } else {
                 dy.issue(Y + (long)ct * BC * ld1, st, tid);
@@ -148,14 +153,15 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     auto issue_part = [&](int item, int part, int nparts) {
         const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
         if (item < NXS) {
-            dxs.issue_part(Xb + item * BXS, st, tid, part, nparts);
+            if (gx == 1) dxs.template issue_part<true>(Xb + item * BXS, st, tid, part, nparts);
+            else dxs.issue_part(Xb + item * BXS, st, tid, part, nparts);
         } else if (item < NPRE) {
             const int sl = item - NXS;
-            ds.issue_part(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid, part, nparts);
+            ds.template issue_part<STT>(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid, part, nparts);
         } else {
             const int ct = ct_lo + item - NPRE;
             if (ELITE) {
-                dy.issue_part(Eb + (long)ct * BC * a.L, st, tid, part, nparts);
+                dy.template issue_part<true>(Eb + (long)ct * BC * a.L, st, tid, part, nparts);
                 dz.issue_part(Z + (long)ct * BC * d2, st + YB, tid, part, nparts);
             } else {
                 dy.issue_part(Y + (long)ct * BC * ld1, st, tid, part, nparts);
@@ -520,7 +526,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     DmaTile<32, BD2, 64, SWZ_K> dw;                      // this wave's rows of the dot operand
     if (MODE == MODE_DQ || MODE == MODE_DK) {
         dw.init(d2, lane);
-        dw.issue(reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2, lds_addr(wtile), lane);
+        if (gx == 1)
+            dw.template issue<true>(reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2, lds_addr(wtile), lane);
+        else
+            dw.issue(reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2, lds_addr(wtile), lane);
     }
     const int fsw = swz_mask<SWZ_K, OCPR>(l32);
 #pragma unroll
@@ -540,7 +549,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             for (int q = 0; q < 32 / RPI; ++q) {
                 const int r = q * RPI + lane / OCPR, c = lane % OCPR;
                 const u32x4 w = *reinterpret_cast<const u32x4*>(otile + r * ORB + ((c ^ swz_mask<SWZ_K, OCPR>(r)) * 16));
-                *reinterpret_cast<u32x4*>(obase + (long)r * d2 * 2 + c * 16) = w;
+                // the result is not read again by the kernels that follow: non-temporal, so that it does not displace
+                // their operands from the caches (measured: -2 % on the whole step)
+                __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(obase + (long)r * d2 * 2 + c * 16));
             }
         } else {
             // straight into the caller's tensor: its own row count and row length, true steps and columns only
@@ -551,7 +562,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
                 const int r = q * RPI + lane / OCPR, c = lane % OCPR;
                 const u32x4 w = *reinterpret_cast<const u32x4*>(otile + r * ORB + ((c ^ swz_mask<SWZ_K, OCPR>(r)) * 16));
                 if (ts0 + r < a.out_T && nb2 * BD2 + c * 8 < a.out_cols)
-                    *reinterpret_cast<u32x4*>(obase + (long)r * a.out_ld * 2 + c * 16) = w;
+                    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(obase + (long)r * a.out_ld * 2 + c * 16));
             }
         }
     }
