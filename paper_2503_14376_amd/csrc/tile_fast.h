@@ -434,7 +434,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
                 for (int q = 0; q < 2; ++q) {
                     const int n = q * 16 + (lane >> 2), c4 = lane & 3;
                     const u32x4 w = *reinterpret_cast<const u32x4*>(et + n * 64 + ((c4 ^ ((n >> 1) & 3)) * 16));
-                    *reinterpret_cast<u32x4*>(eg + ((long)n * a.L + 8 * c4) * 2) = w;
+                    // (non-temporal like the kernel's other results: the dK kernel reads E once, from memory)
+                    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(eg + ((long)n * a.L + 8 * c4) * 2));
                 }
             }
         }
