@@ -19,7 +19,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
 # vector ALU instructions, which cannot read accumulation registers)
 UNITS = [("api.hip", "api.o", []), ("gates.hip", "gates.o", []), ("step.hip", "step.o", []), ("norm.hip", "norm.o", []), ("pad.hip", "pad.o", []),
          ("recurrent.hip", "recurrent.o", ["-mllvm", "-amdgpu-mfma-vgpr-form"])] + [
-    ("tile_inst.hip", "tile_mode%d.o" % m, ["-DTFLA_TILE_MODE=%d" % m]) for m in range(4)]
+    # tile kernels: the start-up loop over X and state slices must unroll completely (its items differ in kind and
+    # index registers by compile-time constants); with the widest shapes its body exceeds the default size limit
+    ("tile_inst.hip", "tile_mode%d.o" % m, ["-DTFLA_TILE_MODE=%d" % m, "-mllvm", "-pragma-unroll-threshold=200000"]) for m in range(4)]
 
 
 def _compile(unit):

@@ -27,6 +27,21 @@ static __device__ unsigned long long tfla_timeline[1 << 18];
 #define TFLA_TL(k)
 #endif
 
+// Order of the first NXS + NKS ring items of a workgroup: the slices of its own X rows ([BR][BXS], read into registers)
+// and the slices of the inter-chunk state ([BD2][BCS] or transposed), interleaved so that every X slice arrives just
+// before the first state slice whose products need it.  The matrix work then starts after one X slice instead of
+// after all of them, and the later X slices load behind the products of the earlier state slices.
+// pre_item(item, BXS, BCS) returns 2 * index + 1 for the X slice `index`, 2 * index for the state slice `index`
+// (closed forms, so that they fold for every unrolled item).
+__host__ __device__ constexpr int pre_item(int item, int BXS, int BCS) {
+    if (BXS >= BCS) {                       // one X slice, then the BXS / BCS state slices it covers
+        const int R = BXS / BCS, grp = item / (R + 1), w = item % (R + 1);
+        return w == 0 ? 2 * grp + 1 : 2 * (grp * R + w - 1);
+    }
+    const int Q = BCS / BXS, grp = item / (Q + 1), w = item % (Q + 1);   // the Q X slices of a state slice, then it
+    return w < Q ? 2 * (grp * Q + w) + 1 : 2 * grp;
+}
+
 // SPLIT: 0 = the whole contraction over D1 in this launch; 1 / 2 = the first / second 512-wide half of a
 // contraction over 1024 columns (rows of the D1-wide operands are 2 D1 apart): the first half stores its raw fp32
 // accumulators, the second adds them to its own before the epilogue.
@@ -127,14 +142,16 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 
     auto issue = [&](int item) {
         const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
-        if (item < NXS) {
-            // the workgroup's own rows: no other workgroup reads them when its block covers all output columns
-            if (gx == 1) dxs.template issue<true>(Xb + item * BXS, st, tid);
-            else dxs.issue(Xb + item * BXS, st, tid);
-        } else if (item < NPRE) {
-            const int sl = item - NXS;
-            // (state slices of the dQ / dK kernels carry the hint too: measured, -3 us on dQ)
-            ds.template issue<STT>(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid);
+        if (item < NPRE) {
+            const int pi = pre_item(item, BXS, BCS), sl = pi >> 1;
+            if (pi & 1) {
+                // the workgroup's own rows: no other workgroup reads them when its block covers all output columns
+                if (gx == 1) dxs.template issue<true>(Xb + sl * BXS, st, tid);
+                else dxs.issue(Xb + sl * BXS, st, tid);
+            } else {
+                // (state slices of the dQ / dK kernels carry the hint too: measured, -3 us on dQ)
+                ds.template issue<STT>(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid);
+            }
         } else {
             const int ct = ct_lo + item - NPRE;
             if (ELITE) {
@@ -152,12 +169,14 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     // the same, spread over `nparts` calls that are placed between matrix instructions
     auto issue_part = [&](int item, int part, int nparts) {
         const uint32_t st = smem_a + (uint32_t)(item % NS) * STAGE;
-        if (item < NXS) {
-            if (gx == 1) dxs.template issue_part<true>(Xb + item * BXS, st, tid, part, nparts);
-            else dxs.issue_part(Xb + item * BXS, st, tid, part, nparts);
-        } else if (item < NPRE) {
-            const int sl = item - NXS;
-            ds.template issue_part<STT>(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid, part, nparts);
+        if (item < NPRE) {
+            const int pi = pre_item(item, BXS, BCS), sl = pi >> 1;
+            if (pi & 1) {
+                if (gx == 1) dxs.template issue_part<true>(Xb + sl * BXS, st, tid, part, nparts);
+                else dxs.issue_part(Xb + sl * BXS, st, tid, part, nparts);
+            } else {
+                ds.template issue_part<STT>(St + (STT ? (long)sl * BCS * d2 : (long)sl * BCS), st, tid, part, nparts);
+            }
         } else {
             const int ct = ct_lo + item - NPRE;
             if (ELITE) {
@@ -176,7 +195,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         int p = 0;
 #pragma unroll
         for (int j = 1; j <= NS - 2; ++j)
-            if (i + j < NI) p += (i + j < NXS) ? CX : ((i + j < NPRE) ? CS : CT);
+            if (i + j < NI) p += (i + j < NPRE) ? ((pre_item(i + j, BXS, BCS) & 1) ? CX : CS) : CT;
         return p;
     };
 
@@ -211,23 +230,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         if (p < NI) issue(p);
     TFLA_TL(1);
 
-    // ---------------- X fragments of the wavefront's 32 rows (lane: row l32, k-group g)
+    // ---------------- the workgroup's X rows (fragments of the wavefront's 32 rows: lane = row l32, k-group g) and the
+    // inter-chunk part acc = X_r St, slice by slice in the order pre_item() gives
+    static_assert(BXS >= BCS ? (BXS % BCS == 0) : (BCS % BXS == 0), "slice widths nest");
     frag xf[KS1];
-    {
-        KFragReader<BXS> rx;  rx.init(l32, g);
-#pragma unroll
-        for (int i = 0; i < NXS; ++i) {
-            wait_vmcnt_dyn(pending_after(i));
-            // the fragment reads of the previous slice have left LDS before its stage is refilled
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            barrier_nofence();
-            if (i + NS - 1 < NI) issue(i + NS - 1);
-            const char* sb = smem + (i % NS) * STAGE;
-#pragma unroll
-            for (int ks = 0; ks < BXS / 16; ++ks) xf[i * (BXS / 16) + ks].v = rx.load(sb, ks, wave);
-        }
-    }
-
+    KFragReader<BXS> rx;   rx.init(l32, g);
     KFragReader<BCS> rs_;  rs_.init(l32, g);
     KFragReader<D1> ry;    ry.init(l32, g);
     TFragReader<BD2> rz;   rz.init(lane, 4);
@@ -239,57 +246,65 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
 
-    // ---------------- inter-chunk part: acc = X_r St
 #pragma unroll
-    for (int i = 0; i < NKS; ++i) {
-        wait_vmcnt_dyn(pending_after(NXS + i));
-        if (i == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    for (int i = 0; i < NPRE; ++i) {
+        const int pi = pre_item(i, BXS, BCS), sl = pi >> 1;
+        wait_vmcnt_dyn(pending_after(i));
+        // the fragment reads of an X slice (not consumed by any instruction yet) have left LDS before its stage is refilled
+        if (i == 0 || (pre_item(i > 0 ? i - 1 : 0, BXS, BCS) & 1)) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         barrier_nofence();
-        const bool req = NXS + i + NS - 1 < NI;
-        const char* sb = smem + ((NXS + i) % NS) * STAGE;
-        constexpr int KSS = BCS / 16, NF = KSS * NB;
-        if constexpr (OCC == 1) {
-            // one wavefront per SIMD: nothing else hides the time the request spends in the memory
-            // pipeline's queue, so it is spread between the matrix instructions; the fragments of k step
-            // ks + 1 are read while the matrix instructions of k step ks run
-            frag b[2][NB];
+        const char* sb = smem + (i % NS) * STAGE;
+        if (pi & 1) {
+            if (i + NS - 1 < NI) issue(i + NS - 1);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) b[0][nb].v = STT ? rzn.load(sb, nb, 0, 4) : rs_.load(sb, 0, nb);
+            for (int ks = 0; ks < BXS / 16; ++ks) xf[sl * (BXS / 16) + ks].v = rx.load(sb, ks, wave);
+        } else {
+            const bool req = i + NS - 1 < NI;
+            constexpr int KSS = BCS / 16, NF = KSS * NB;
+            if constexpr (OCC == 1) {
+                // one wavefront per SIMD: nothing else hides the time the request spends in the memory
+                // pipeline's queue, so it is spread between the matrix instructions; the fragments of k step
+                // ks + 1 are read while the matrix instructions of k step ks run
+                frag b[2][NB];
 #pragma unroll
-            for (int ks = 0; ks < KSS; ++ks) {
-                if (ks + 1 < KSS) {
+                for (int nb = 0; nb < NB; ++nb) b[0][nb].v = STT ? rzn.load(sb, nb, 0, 4) : rs_.load(sb, 0, nb);
+#pragma unroll
+                for (int ks = 0; ks < KSS; ++ks) {
+                    if (ks + 1 < KSS) {
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            b[(ks + 1) & 1][nb].v = STT ? rzn.load(sb, nb, 16 * (ks + 1), 16 * (ks + 1) + 4) : rs_.load(sb, ks + 1, nb);
+                    }
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks & 1][nb], xf[sl * KSS + ks], acc[nb]);
+                    if (req) issue_part(i + NS - 1, ks, KSS);
+                }
+            } else {
+                if (req) issue(i + NS - 1);
+                frag b[KSS][NB];
+#pragma unroll
+                for (int ks = 0; ks < KSS; ++ks)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
-                        b[(ks + 1) & 1][nb].v = STT ? rzn.load(sb, nb, 16 * (ks + 1), 16 * (ks + 1) + 4) : rs_.load(sb, ks + 1, nb);
+                        b[ks][nb].v = STT ? rzn.load(sb, nb, 16 * ks, 16 * ks + 4) : rs_.load(sb, ks, nb);
+#pragma unroll
+                for (int ks = 0; ks < KSS; ++ks)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks][nb], xf[sl * KSS + ks], acc[nb]);
+                // LDS reads run PF fragments ahead of the MFMAs that consume them
+                constexpr int PF = NF < 4 ? NF : 4;
+                constexpr int DSR = STT ? 2 : 1;            // LDS reads per fragment
+#pragma unroll
+                for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);
+#pragma unroll
+                for (int q = 0; q < NF - PF; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);
                 }
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks & 1][nb], xf[i * KSS + ks], acc[nb]);
-                if (req) issue_part(NXS + i + NS - 1, ks, KSS);
+                for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             }
-        } else {
-            if (req) issue(NXS + i + NS - 1);
-            frag b[KSS][NB];
-#pragma unroll
-            for (int ks = 0; ks < KSS; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    b[ks][nb].v = STT ? rzn.load(sb, nb, 16 * ks, 16 * ks + 4) : rs_.load(sb, ks, nb);
-#pragma unroll
-            for (int ks = 0; ks < KSS; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[nb] = E::mma(b[ks][nb], xf[i * KSS + ks], acc[nb]);
-            // LDS reads run PF fragments ahead of the MFMAs that consume them
-            constexpr int PF = NF < 4 ? NF : 4;
-            constexpr int DSR = STT ? 2 : 1;            // LDS reads per fragment
-#pragma unroll
-            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);
-#pragma unroll
-            for (int q = 0; q < NF - PF; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);
-            }
-#pragma unroll
-            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+
         }
     }
     TFLA_TL(2);
@@ -336,6 +351,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     }
     for (int ct = ct_lo; ct < ct_hi; ++ct) {
         const int i = NPRE + ct - ct_lo;
+        __builtin_assume(i >= NPRE);            // (column tiles only from here on: lets the item-kind tests fold)
         wait_vmcnt_dyn(pending_after(i));
         barrier_nofence();
         const bool req = i + NS - 1 < NI;
