@@ -201,6 +201,10 @@ struct TileArgs {
     // fp32 kernels: rounding remainders of the row and column exponents (the weight is exp2 of the sum of all four),
     // and where MODE_H leaves the remainder that belongs to wrowB_out; NULL = none
     const float* wrow_lo; const float* wcol_lo; float* wrowB_lo_out;
+    // bf16 kernels, filled in by the launcher: what the decomposition of the linear workgroup id divides by --
+    // batch*head count, slices per XCD, and for each divisor its log2 when it is a power of two, else -1
+    // (a division by a run-time value costs the start of every workgroup some forty instructions)
+    int dec_bh, dec_bpx, sh_gx, sh_gy, sh_bpx, sh_nc;
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
 // d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16

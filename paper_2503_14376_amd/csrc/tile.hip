@@ -292,9 +292,16 @@ __global__ void __launch_bounds__(NW * 64) tile_kernel(TileArgs a) {
 
 // ------------------------------------------------------------------------------------------
 template <typename DT, int D1, int BD2, int NW, int MODE, int SPLIT = 0>
-static hipError_t launch_tile_t(const TileArgs& a, int BH, hipStream_t s) {
+static hipError_t launch_tile_t(const TileArgs& a0, int BH, hipStream_t s) {
+    TileArgs a = a0;
     dim3 grid((unsigned)((long)(a.d2 / BD2) * (a.L / (32 * NW)) * BH * a.Nc));
     if constexpr (sizeof(DT) == 2) {
+        // what the kernel's decomposition of the linear workgroup id divides by
+        auto log2_or_neg = [](int v) { return (v > 0 && (v & (v - 1)) == 0) ? __builtin_ctz((unsigned)v) : -1; };
+        a.dec_bh = BH;
+        a.dec_bpx = BH % 8 == 0 ? BH / 8 : 1;
+        a.sh_gx = log2_or_neg(a.d2 / BD2); a.sh_gy = log2_or_neg(a.L / (32 * NW));
+        a.sh_bpx = log2_or_neg(a.dec_bpx); a.sh_nc = log2_or_neg(a.Nc);
         // two workgroups per CU when the accumulator is narrow enough for 256 registers per lane
         constexpr int OCC = (BD2 <= 128 && D1 <= 256) ? 2 : 1;
         // dQ / dK share the weighted matrix E through memory only where the contraction that forms it is wide

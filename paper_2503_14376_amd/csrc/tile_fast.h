@@ -96,19 +96,29 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     // linear id -> (column block, row block, chunk, batch*head), column blocks fastest
     const unsigned nwg = gridDim.x, gx = (unsigned)a.d2 / BD2, gy = (unsigned)a.L / (32 * NW);
     unsigned wg = xcd_remap(blockIdx.x, nwg);
-    const int nb2 = __builtin_amdgcn_readfirstlane((int)(wg % gx)); wg /= gx;
-    const int rbi = __builtin_amdgcn_readfirstlane((int)(wg % gy)); wg /= gy;
+    // quotient and remainder by a divisor whose log2 the launcher supplies when it has one
+    auto divmod = [](unsigned n, unsigned d, int sh, unsigned& rem) {
+        const unsigned q = sh >= 0 ? n >> sh : n / d;
+        rem = n - q * d;
+        return q;
+    };
+    unsigned rem;
+    wg = divmod(wg, gx, a.sh_gx, rem);
+    const int nb2 = __builtin_amdgcn_readfirstlane((int)rem);
+    wg = divmod(wg, gy, a.sh_gy, rem);
+    const int rbi = __builtin_amdgcn_readfirstlane((int)rem);
     const int rb = UPPER ? rbi : (int)gy - 1 - rbi;      // row blocks with more column tiles first
     // Order in time: every XCD walks the chunks of its own (batch, head) slices together, chunk by chunk, in
     // the direction a.kc_desc gives -- the launcher picks the direction that starts where the kernel before
     // this one stopped, so that what that kernel read or wrote last is still in the memory-side cache.
     // bpx = slices per XCD (the XCD's contiguous range of ids then covers exactly its slices)
-    const unsigned bhn = nwg / (gx * gy * (unsigned)a.Nc);
-    const unsigned bpx = (bhn % 8u == 0u) ? bhn / 8u : 1u;
-    const unsigned bl = wg % bpx; wg /= bpx;
-    const int kci = __builtin_amdgcn_readfirstlane((int)(wg % a.Nc));
+    const unsigned bhn = (unsigned)a.dec_bh, bpx = (unsigned)a.dec_bpx;
+    wg = divmod(wg, bpx, a.sh_bpx, rem);
+    const unsigned bl = rem;
+    wg = divmod(wg, (unsigned)a.Nc, a.sh_nc, rem);
+    const int kci = __builtin_amdgcn_readfirstlane((int)rem);
     const int kc = a.kc_desc ? a.Nc - 1 - kci : kci;
-    const int bh = __builtin_amdgcn_readfirstlane((int)((wg / a.Nc) * bpx + bl));
+    const int bh = __builtin_amdgcn_readfirstlane((int)(wg * bpx + bl));
     const long tbase = (long)bh * a.T + (long)kc * a.L;
     const int r0 = rb * BR, wr0 = r0 + wave * 32;
     const int d2 = a.d2;
@@ -595,7 +605,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
                      acc[nb][4 * j + 2] * bf16_lo_to_f32(w.y) + acc[nb][4 * j + 3] * bf16_hi_to_f32(w.y);
             }
         d += __shfl_xor(d, 32, 64);
-        if (g == 0) a.dotpart[(long)nb2 * (long)(nwg / (gx * gy * (unsigned)a.Nc)) * a.T + t] = d;
+        if (g == 0) a.dotpart[(long)nb2 * (long)bhn * a.T + t] = d;
     }
     TFLA_TL(5);
 #ifdef TFLA_TIMELINE
