@@ -322,7 +322,7 @@ static hipError_t launch_tile_t(const TileArgs& a0, int BH, hipStream_t s) {
 template <typename DT, int D1, int MODE, int SPLIT = 0>
 static hipError_t launch_tile_d1(const TileArgs& a, int BH, int bd2, hipStream_t s) {
     if (a.L % 128 == 0) {
-        if constexpr (sizeof(DT) == 2 && D1 > 256 && SPLIT == 0) {
+        if constexpr (sizeof(DT) == 2 && D1 > 256 && SPLIT == 0 && (MODE == MODE_DQ || MODE == MODE_DK)) {   // see tile_bd2()
             if (bd2 == 256) return launch_tile_t<DT, D1, 256, 4, MODE>(a, BH, s);
         }
         if (bd2 == 128) return launch_tile_t<DT, D1, 128, 4, MODE, SPLIT>(a, BH, s);

@@ -256,6 +256,12 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
 
+    // mLSTMexp forward: accumulator of the normaliser's inter-chunk dot q~ . n_{k-1} (see below)
+    f32x16 an;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) an[v] = 0.0f;
+    const char* nrow = reinterpret_cast<const char*>(ldsN) + (l32 & 1) * (D1 * 2) + 16 * g;
+
 #pragma unroll
     for (int i = 0; i < NPRE; ++i) {
         const int pi = pre_item(i, BXS, BCS), sl = pi >> 1;
@@ -268,6 +274,22 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             if (i + NS - 1 < NI) issue(i + NS - 1);
 #pragma unroll
             for (int ks = 0; ks < BXS / 16; ++ks) xf[sl * (BXS / 16) + ks].v = rx.load(sb, ks, wave);
+            if (MODE == MODE_H) {
+                if (a.variant == 0) {
+                    // this slice's share of q~ . n_{k-1}: it fills matrix-unit time that the loads leave idle here
+                    // (n has landed: it was requested before the ring and this is past the first barrier)
+#pragma unroll
+                    for (int ks = sl * (BXS / 16); ks < (sl + 1) * (BXS / 16); ++ks) {
+                        frag bn;
+                        bn.v = *reinterpret_cast<const bf16x8*>(nrow + 32 * ks);
+                        if (l32 >= 2) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) bn.v[e] = (bf16_t)0.0f;
+                        }
+                        an = E::mma(bn, xf[ks], an);
+                    }
+                }
+            }
         } else {
             const bool req = i + NS - 1 < NI;
             constexpr int KSS = BCS / 16, NF = KSS * NB;
@@ -331,20 +353,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             // q~ . n_{k-1} on the matrix unit: n sits in LDS as two bf16 rows (value, remainder), which enter as
             // rows 0 and 1 of an otherwise empty 32-row operand next to the X fragments in registers; the
             // two result columns of a row add up to its dot product
-            f32x16 an;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) an[v] = 0.0f;
-            const char* nrow = reinterpret_cast<const char*>(ldsN) + (l32 & 1) * (D1 * 2) + 16 * g;
-#pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) {
-                frag bn;
-                bn.v = *reinterpret_cast<const bf16x8*>(nrow + 32 * ks);
-                if (l32 >= 2) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) bn.v[e] = (bf16_t)0.0f;
-                }
-                an = E::mma(bn, xf[ks], an);
-            }
+            // (the products were formed slice by slice while the X rows arrived, see above)
             float dot = g == 0 ? an[0] + an[1] : 0.0f;
             dot += __shfl_xor(dot, 32, 64);
             nrm = dot * srl;
