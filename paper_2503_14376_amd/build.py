@@ -21,7 +21,9 @@ UNITS = [("api.hip", "api.o", []), ("gates.hip", "gates.o", []), ("step.hip", "s
          ("recurrent.hip", "recurrent.o", ["-mllvm", "-amdgpu-mfma-vgpr-form"])] + [
     # tile kernels: the start-up loop over X and state slices must unroll completely (its items differ in kind and
     # index registers by compile-time constants); with the widest shapes its body exceeds the default size limit
-    ("tile_inst.hip", "tile_mode%d.o" % m, ["-DTFLA_TILE_MODE=%d" % m, "-mllvm", "-pragma-unroll-threshold=200000"]) for m in range(4)]
+    # (accumulators in ordinary VGPRs as for recurrent.hip: the dK kernel then needs no accumulation registers at all)
+    ("tile_inst.hip", "tile_mode%d.o" % m, ["-DTFLA_TILE_MODE=%d" % m, "-mllvm", "-pragma-unroll-threshold=200000",
+                                            "-mllvm", "-amdgpu-mfma-vgpr-form"]) for m in range(4)]
 
 
 def _compile(unit):
