@@ -358,11 +358,13 @@ template <int MODE>
 hipError_t launch_tile_mode(const TileArgs& a0, int BH, int dtype, hipStream_t s) {
     TileArgs a = a0;
     a.acc_in = nullptr; a.nrm_in = nullptr; a.acc_out = nullptr; a.nrm_out = nullptr;
-    // Chunk order of each kernel of the sequence gates -> recurrence (first to last) -> H and
-    // reversed recurrence (last to first) -> dV -> dQ -> dK: each starts at the end of the sequence where its
-    // predecessor stopped.
+    // Chunk order of each kernel of the sequence gates -> recurrence (first to last) -> H and reversed recurrence
+    // (last to first) -> dV -> dQ -> dK, chosen by measurement (eight of the sixteen combinations on one box):
+    // what matters is that H walks the chunks first to last, like the recurrence before it -- starting with the
+    // states that were stored last (with non-temporal stores) costs 2 % of the step; among the gradient kernels
+    // the differences are a few tenths of a percent, dK walking against dQ being the best.
 #ifndef TFLA_KC_ORDER
-#define TFLA_KC_ORDER 0x5   // bit m = direction of mode m: H descending, dV ascending, dQ descending, dK ascending
+#define TFLA_KC_ORDER 0x8   // bit m = 1: mode m walks the chunks last to first.  H, dV, dQ first to last, dK last to first
 #endif
     a.kc_desc = ((TFLA_KC_ORDER) >> MODE) & 1;
     const int bd2 = tile_bd2(a.d1, a.d2, dtype, MODE, a.L);

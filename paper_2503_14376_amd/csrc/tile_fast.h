@@ -109,8 +109,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     const int rbi = __builtin_amdgcn_readfirstlane((int)rem);
     const int rb = UPPER ? rbi : (int)gy - 1 - rbi;      // row blocks with more column tiles first
     // Order in time: every XCD walks the chunks of its own (batch, head) slices together, chunk by chunk, in
-    // the direction a.kc_desc gives -- the launcher picks the direction that starts where the kernel before
-    // this one stopped, so that what that kernel read or wrote last is still in the memory-side cache.
+    // the direction a.kc_desc gives (the launcher's choice, by measurement).
     // bpx = slices per XCD (the XCD's contiguous range of ids then covers exactly its slices)
     const unsigned bhn = (unsigned)a.dec_bh, bpx = (unsigned)a.dec_bpx;
     wg = divmod(wg, bpx, a.sh_bpx, rem);
