@@ -492,8 +492,12 @@ int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
     TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, dqk * es, dq_p * es, s));
     TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, dqk * es, dq_p * es, s));
     TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, dhv * es, dv_p * es, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
-    TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
+    // per-step scalars need copies only when the sequence itself is padded
+    const bool tpad = Tp != T;
+    if (tpad) {
+        TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
+        TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
+    }
     const float* C0c = C0; const float* n0c = n0;
     if (dpad && C0) {
         TFLA_LAUNCH(K_PAD, launch_pad_rows(C0, p.C0, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
@@ -503,12 +507,12 @@ int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
     float* Cnc = (dpad && Cn) ? p.Cn : Cn;
     float* nnc = (dpad && nn) ? p.nn : nn;
     // (the H kernel stores the true steps and columns straight into the caller's H)
-    const int st = fwd_core(p.q, p.k, p.v, p.ip, p.fp, C0c, n0c, m0, B, NH, Tp, T, dqk, dhv, dq_p, dv_p, chunk, variant, dtype, eps,
-                            softcap, H, Cnc, nnc, mn, n_out ? p.nout : nullptr, m_out ? p.mout : nullptr, workspace,
-                            core_bytes, stream);
+    const int st = fwd_core(p.q, p.k, p.v, tpad ? p.ip : i_pre, tpad ? p.fp : f_pre, C0c, n0c, m0, B, NH, Tp, T, dqk, dhv, dq_p,
+                            dv_p, chunk, variant, dtype, eps, softcap, H, Cnc, nnc, mn, (n_out && tpad) ? p.nout : n_out,
+                            (m_out && tpad) ? p.mout : m_out, workspace, core_bytes, stream);
     if (st != TFLA_OK) return st;
-    if (n_out) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.nout, n_out, d.BH, T, Tp, s));
-    if (m_out) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.mout, m_out, d.BH, T, Tp, s));
+    if (n_out && tpad) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.nout, n_out, d.BH, T, Tp, s));
+    if (m_out && tpad) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.mout, m_out, d.BH, T, Tp, s));
     if (dpad && Cn) TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.Cn, Cn, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
     if (dpad && nn) TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.nn, nn, d.BH, dqk, dq_p, s));
     return TFLA_OK;
@@ -547,6 +551,7 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const int Tp = d.T, es = (int)d.esz, eq = dqk * es, ev = dhv * es, eqp = dq_p * es, evp = dv_p * es;
     const bool dpad = dq_p != dqk || dv_p != dhv;
+    const bool tpad = Tp != T;      // per-step scalars need copies only when the sequence itself is padded
     // The forward call left its padded copies of q, k, v and the gate pre-activations behind its core workspace:
     // a backward call that is handed that workspace (whole) reads them there instead of copying again.
     const void *pq = p.q, *pk = p.k, *pv = p.v;
@@ -559,11 +564,14 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
         TFLA_LAUNCH(K_PAD, launch_pad_rows(q, p.q, d.BH, T, Tp, eq, eqp, s));
         TFLA_LAUNCH(K_PAD, launch_pad_rows(k, p.k, d.BH, T, Tp, eq, eqp, s));
         TFLA_LAUNCH(K_PAD, launch_pad_rows(v, p.v, d.BH, T, Tp, ev, evp, s));
-        TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
-        TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
+        if (tpad) {
+            TFLA_LAUNCH(K_PAD, launch_pad_scalar(i_pre, p.ip, d.BH, T, Tp, 0.0f, s));
+            TFLA_LAUNCH(K_PAD, launch_pad_scalar(f_pre, p.fp, d.BH, T, Tp, 0.0f, s));
+        }
     }
+    if (!tpad) { pip = i_pre; pfp = f_pre; }
     TFLA_LAUNCH(K_PAD, launch_pad_rows(dH, p.dH, d.BH, T, Tp, ev, evp, s));
-    if (is_exp) {
+    if (is_exp && tpad) {
         // denominators of the padding steps: max{|1|, exp(0)} -- any finite non-zero value would do
         TFLA_LAUNCH(K_PAD, launch_pad_scalar(n_out, p.nout, d.BH, T, Tp, 1.0f, s));
         TFLA_LAUNCH(K_PAD, launch_pad_scalar(m_out, p.mout, d.BH, T, Tp, 0.0f, s));
@@ -579,13 +587,17 @@ int bwd_impl(const void* q, const void* k, const void* v, const float* i_pre, co
         dCnc = p.dCn;
     }
     float* dC0c = (dpad && dC0) ? p.dC0 : dC0;
-    const int st = bwd_core(pq, pk, pv, pip, pfp, C0c, n0c, m0, is_exp ? p.nout : nullptr, is_exp ? p.mout : nullptr,
-                            p.dH, dCnc, B, NH, Tp, T, dqk, dhv, dq_p, dv_p, chunk, variant, dtype, eps, softcap, dq, dk, dv,
-                            p.di, p.df, dC0c, fwd_workspace, fwd_workspace_bytes, workspace, core_bytes, stream);
+    const float* noc = !is_exp ? nullptr : (tpad ? p.nout : n_out);
+    const float* moc = !is_exp ? nullptr : (tpad ? p.mout : m_out);
+    const int st = bwd_core(pq, pk, pv, pip, pfp, C0c, n0c, m0, noc, moc, p.dH, dCnc, B, NH, Tp, T, dqk, dhv, dq_p, dv_p,
+                            chunk, variant, dtype, eps, softcap, dq, dk, dv, tpad ? p.di : d_i_pre, tpad ? p.df : d_f_pre,
+                            dC0c, fwd_workspace, fwd_workspace_bytes, workspace, core_bytes, stream);
     if (st != TFLA_OK) return st;
     // (the gradient kernels stored the true steps and columns straight into the caller's dq, dk, dv)
-    TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.di, d_i_pre, d.BH, T, Tp, s));
-    TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.df, d_f_pre, d.BH, T, Tp, s));
+    if (tpad) {
+        TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.di, d_i_pre, d.BH, T, Tp, s));
+        TFLA_LAUNCH(K_PAD, launch_unpad_scalar(p.df, d_f_pre, d.BH, T, Tp, s));
+    }
     if (dpad && dC0) TFLA_LAUNCH(K_PAD, launch_unpad_rows(p.dC0, dC0, d.BH, dqk, dq_p, dhv * 4, dv_p * 4, s));
     return TFLA_OK;
 }
