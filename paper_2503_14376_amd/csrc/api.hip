@@ -415,9 +415,10 @@ int bwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
 
 // ---- sequence lengths that do not fill the last chunk, head dimensions between the kernels' own -------
 // The cores work on whole chunks and on head dimensions 64, 128, 256, 512 (bf16 also 1024).  For any other T or head
-// dimension the entry points copy the inputs into zero-padded buffers behind the core's own workspace,
-// run the core there (Tvalid = T, the 1/sqrt(dqk) of the true dqk), and copy the true part of the outputs
-// back.  `d` below always describes the padded problem.
+// dimension the entry points copy q, k, v (and dH) into zero-padded buffers behind the core's own workspace and
+// run the core there (Tvalid = T, the 1/sqrt(dqk) of the true dqk).  The tiled kernels store the true steps and
+// columns of H, dq, dk, dv straight into the caller's tensors; per-step scalars go through padded copies only when
+// the sequence itself is padded, states only when a head dimension is.  `d` below always describes the padded problem.
 struct PadFwd {
     void *q, *k, *v;
     float *ip, *fp, *nout, *mout, *C0, *n0, *Cn, *nn;
