@@ -81,6 +81,15 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     constexpr int EPI = ((MODE == MODE_DQ || MODE == MODE_DK) ? 2 : 1) * NW * 32 * BD2 * 2;
     constexpr int SMEM = NS * STAGE > EPI ? NS * STAGE : EPI;
     static_assert(SMEM <= BUDGET, "LDS budget");
+    // The epilogue's per-wave tiles ([32][BD2] bf16: the output block on its way out and, for dQ / dK, the wave's rows
+    // of the dot operand) live in slots of the ring's memory.  Slots are numbered from the stage after the one that
+    // holds the last ring item: the first (NS - 1) SPS of them are free while that item is being multiplied, so the dot
+    // operand (slots 0 .. NW-1) is requested then and its latency hides behind the last tile; the output tiles take
+    // the slots NW .. 2 NW - 1 once every wave has left the ring.
+    constexpr int SLOT = 32 * BD2 * 2, SPS = STAGE / SLOT >= 1 ? STAGE / SLOT : 1;
+    // (not where a slot is larger than a stage, and not in the first half of a split contraction, which has no epilogue)
+    constexpr bool WPRE = (MODE == MODE_DQ || MODE == MODE_DK) && SPLIT != 1 && STAGE >= SLOT && (NS - 1) * SPS >= NW &&
+                          NS * SPS >= 2 * NW;
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     __shared__ __attribute__((aligned(1024))) char ldsE[EWRITE ? ESTG : 16];
     __shared__ __attribute__((aligned(256))) float ldsW[NS][NW][64];   // column weights of a tile, one copy per wave
@@ -373,6 +382,17 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         wait_vmcnt_dyn(pending_after(i));
         barrier_nofence();
         const bool req = i + NS - 1 < NI;
+        if constexpr (WPRE) {
+            if (i == NI - 1) {
+                const int sl = wave, stg = (i + 1 + sl / SPS) % NS;
+                DmaTile<32, BD2, 64, SWZ_K> dw;
+                dw.init(d2, lane);
+                const bf16_t* wsrc = reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2;
+                const uint32_t wdst = smem_a + (uint32_t)(stg * STAGE + (sl % SPS) * SLOT);
+                if (gx == 1) dw.template issue<true>(wsrc, wdst, lane);
+                else dw.issue(wsrc, wdst, lane);
+            }
+        }
         const int cs = ct * BC;
         const bool masked = UPPER ? (cs + 31 < wr0) : (cs > wr0 + 31);   // fully masked for this wave
         // with one wavefront per SIMD the request is spread between the matrix instructions below
@@ -556,10 +576,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     // row-contiguous stores: per wave a [32][BD2] bf16 tile with XOR-swizzled 16-byte chunks.
     barrier_nofence();                                   // every wave is done reading the ring
     constexpr int OCPR = BD2 / 8, ORB = BD2 * 2;         // chunks and bytes per tile row
-    char* otile = smem + wave * (32 * ORB);
-    char* wtile = smem + NW * (32 * ORB) + wave * (32 * ORB);
-    DmaTile<32, BD2, 64, SWZ_K> dw;                      // this wave's rows of the dot operand
-    if (MODE == MODE_DQ || MODE == MODE_DK) {
+    auto slot_at = [&](int sl) { return smem + ((NI + sl / SPS) % NS) * STAGE + (sl % SPS) * SLOT; };
+    char* otile = WPRE ? slot_at(NW + wave) : smem + wave * (32 * ORB);
+    char* wtile = WPRE ? slot_at(wave) : smem + NW * (32 * ORB) + wave * (32 * ORB);
+    if ((MODE == MODE_DQ || MODE == MODE_DK) && !WPRE) {
+        DmaTile<32, BD2, 64, SWZ_K> dw;                  // this wave's rows of the dot operand
         dw.init(d2, lane);
         if (gx == 1)
             dw.template issue<true>(reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2, lds_addr(wtile), lane);
@@ -602,7 +623,11 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
         }
     }
     if (MODE == MODE_DQ || MODE == MODE_DK) {
-        wait_vmcnt<0>();                                 // the dot operand has landed (and the stores are out)
+        // the dot operand has landed: its loads are older than the output stores above (and than the E stores of the
+        // last tile), which may still be on their way.  (A padded problem issues a store only where a lane has
+        // something to store, so their number is not known here.)
+        if constexpr (PADOUT) wait_vmcnt<0>();
+        else wait_vmcnt<32 / (64 / OCPR)>();
         float d = 0.0f;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
