@@ -35,8 +35,8 @@ Readings of the paper (each also listed in the design notes):
     normaliser 1 (App. D.2, "Normalizers of mLSTMexp and mLSTMsig");
   * eps is added to max{|n^T q~|, exp(-m)}; eps = 0 is the paper's formula.
 
-Parity unpinned: behaviour for gate pre-activations far outside the tested
-ranges (beyond |x| ~ 40) is only checked for finiteness.
+Gate pre-activations far outside the benchmark's ranges (|x| up to 300) are pinned
+against the unstabilised cell evaluated in 150-digit arithmetic (pin P8 of the tests).
 """
 from __future__ import annotations
 

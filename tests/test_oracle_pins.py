@@ -10,6 +10,8 @@ P5  continuation across a split of the sequence
 P6  backward: central finite differences of the frozen-normaliser objective;
     chunkwise backward (App. B.3) == definition, for several L
 P7  the count model reproduces the numbers the paper prints
+P8  gate pre-activations up to |x| = 300: every forward form and both backward definitions against the
+    unstabilised cell in 150-digit arithmetic
 """
 import math
 import os
@@ -372,3 +374,92 @@ def test_p7_recurrent_step_memory_operations():
     # at the 7B head shape the matrix memory is > 99 % of the traffic: the step is bound by 2 d_qk d_hv floats
     tot = cm.bytes_recurrent_step_exp(256, 512)
     assert 2 * 256 * 512 * 4 / tot > 0.99
+
+
+# ---------------------------------------------------------------- P8
+def _mp_cell(d, dH, variant, s, digits=150):
+    """The unstabilised cell (App. D.1, first equation) and the frozen-normaliser gradients of
+    l = sum_t <dH_t, H_t>, written as explicit double sums over (t, j) in arbitrary-precision arithmetic:
+    no max state, no log-domain reordering, so that nothing of the oracle's stabilisation is shared.
+    Zero initial state.  Returns floats."""
+    mp = pytest.importorskip("mpmath")
+    mp.mp.dps = digits
+    F = mp.mpf
+    q, k, v = d["q"][s], d["k"][s], d["v"][s]
+    T, dqk = q.shape
+    dhv = v.shape[1]
+    ip = [F(float(x)) for x in d["i_pre"][s]]
+    fp = [F(float(x)) for x in d["f_pre"][s]]
+    sig = lambda x: 1 / (1 + mp.exp(-x))
+    fg = [sig(x) for x in fp]
+    ig = [mp.exp(x) if variant == EXP else sig(x) for x in ip]
+    rs = 1 / mp.sqrt(dqk)
+    qs = [[F(float(q[t, c])) * rs for c in range(dqk)] for t in range(T)]
+    kk = [[F(float(k[t, c])) for c in range(dqk)] for t in range(T)]
+    vv = [[F(float(v[t, c])) for c in range(dhv)] for t in range(T)]
+    gg = [[F(float(dH[s][t, c])) for c in range(dhv)] for t in range(T)]
+    # w[t][j] = ig_j * prod_{j < r <= t} fg_r
+    w = [[F(0)] * T for _ in range(T)]
+    for t in range(T):
+        for j in range(t + 1):
+            p = ig[j]
+            for r in range(j + 1, t + 1):
+                p *= fg[r]
+            w[t][j] = p
+    dot = lambda a, b: sum(x * y for x, y in zip(a, b))
+    H = np.zeros((T, dhv)); den = [F(1)] * T
+    for t in range(T):
+        num = [sum(w[t][j] * dot(qs[t], kk[j]) * vv[j][c] for j in range(t + 1)) for c in range(dhv)]
+        nrm = sum(w[t][j] * dot(qs[t], kk[j]) for j in range(t + 1))
+        den[t] = max(abs(nrm), F(1)) if variant == EXP else F(1)
+        H[t] = [float(x / den[t]) for x in num]
+    dq = np.zeros((T, dqk)); dk = np.zeros((T, dqk)); dv = np.zeros((T, dhv)); di = np.zeros(T); df = np.zeros(T)
+    E = [[F(0)] * T for _ in range(T)]              # gradient w.r.t. the log of w[t][j]
+    for t in range(T):
+        for j in range(t + 1):
+            E[t][j] = w[t][j] * dot(qs[t], kk[j]) * dot(gg[t], vv[j]) / den[t]
+    for t in range(T):
+        for c in range(dqk):
+            dq[t, c] = float(rs * sum(w[t][j] * dot(gg[t], vv[j]) / den[t] * kk[j][c] for j in range(t + 1)))
+    for j in range(T):
+        for c in range(dqk):
+            dk[j, c] = float(sum(w[t][j] * dot(gg[t], vv[j]) / den[t] * qs[t][c] for t in range(j, T)))
+        for c in range(dhv):
+            dv[j, c] = float(sum(w[t][j] * dot(qs[t], kk[j]) * gg[t][c] / den[t] for t in range(j, T)))
+        dlog_i = sum(E[t][j] for t in range(j, T))                      # d/d log(ig_j)
+        di[j] = float(dlog_i if variant == EXP else dlog_i * sig(-ip[j]))
+        dlog_f = sum(E[t][jj] for t in range(j, T) for jj in range(j))   # fg_j sits in w[t][jj] for jj < j <= t
+        df[j] = float(dlog_f * sig(-fp[j]))
+    return dict(H=H, dq=dq, dk=dk, dv=dv, di=di, df=df)
+
+
+@pytest.mark.parametrize("variant", [EXP, SIG])
+def test_p8_extreme_gate_preactivations_against_arbitrary_precision(variant):
+    """Gate pre-activations far outside the benchmark's range (|x| up to 300: exp(i~) up to 1e130, forget gates
+    down to 1e-130 and up to 1 - 1e-130, resets next to saturated steps): the stabilised fp64 recurrence, the
+    quadratic form, the chunkwise form and the backward definitions against the unstabilised cell evaluated
+    with 150 digits."""
+    g = np.random.default_rng(80)
+    S, T, dqk, dhv = 2, 9, 3, 2
+    d = dict(q=g.standard_normal((S, T, dqk)), k=g.standard_normal((S, T, dqk)), v=g.standard_normal((S, T, dhv)),
+             i_pre=np.array([[300.0, -300.0, 45.0, 0.0, -60.0, 120.0, 119.0, -5.0, 250.0],
+                             [-250.0, -249.0, -300.0, 10.0, 80.0, -80.0, 0.5, 299.0, -299.0]]),
+             f_pre=np.array([[0.0, 300.0, -300.0, 50.0, -50.0, 3.0, 200.0, -120.0, 1.0],
+                             [300.0, 299.0, 60.0, -300.0, -2.0, 40.0, -40.0, 100.0, -100.0]]),
+             C0=None, n0=None, m0=None)
+    dH = g.standard_normal((S, T, dhv))
+    rec = orc.recurrent_fwd(**d, variant=variant, eps=0.0)
+    quad = orc.quadratic_fwd(**d, variant=variant, eps=0.0)
+    bq = orc.quadratic_bwd(**d, dH=dH, variant=variant, eps=0.0)
+    for L in (1, 3, 9):
+        ch = orc.chunkwise_fwd(**d, variant=variant, eps=0.0, chunk=L)
+        bc = orc.chunkwise_bwd(**d, dH=dH, variant=variant, eps=0.0, chunk=L)
+        for s in range(S):
+            ref = _mp_cell(d, dH, variant, s)
+            for got in (rec["H"][s], quad["H"][s], ch["H"][s]):
+                assert np.all(np.isfinite(got))
+                close(got, ref["H"], 1e-11)
+            for b in (bq, bc):
+                for name in ("dq", "dk", "dv", "di", "df"):
+                    assert np.all(np.isfinite(b[name][s])), name
+                    close(b[name][s], ref[name], 1e-10)
