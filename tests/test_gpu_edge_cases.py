@@ -72,7 +72,8 @@ def test_batch_head_counts_not_multiple_of_eight(B, NH):
 
 @pytest.mark.parametrize("variant", [wl.EXP, wl.SIG])
 @pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
-@pytest.mark.parametrize("case", ["reset_every_step", "never_forget", "input_gate_closed", "zero_queries", "mixed_resets"])
+@pytest.mark.parametrize("case", ["reset_every_step", "never_forget", "input_gate_closed", "zero_queries", "mixed_resets",
+                                  "extreme_mix"])
 def test_degenerate_gates(variant, dtype, case):
     w = wl.small(variant, dtype, B=1, NH=2, T=256, dqk=64, dhv=128, chunk=64, seed=77)
     d = wl.make_inputs(w)
@@ -84,6 +85,12 @@ def test_degenerate_gates(variant, dtype, case):
         d["i_pre"][:] = -30.0
     elif case == "zero_queries":
         d["q"][:] = 0.0
+    elif case == "extreme_mix":           # |x| = 80 at scattered steps: exp(i~) ~ 5e34, resets next to saturated steps
+        g = np.random.default_rng(78)
+        for name in ("i_pre", "f_pre"):
+            u = g.random(d[name].shape)
+            d[name][u < 0.04] = -80.0
+            d[name][u > 0.96] = 80.0
     else:                                  # resets at a few steps, open gates elsewhere
         d["f_pre"][:] = 6.0
         d["f_pre"][..., ::37] = -40.0
