@@ -282,6 +282,15 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
             if (i + NS - 1 < NI) issue(i + NS - 1);
 #pragma unroll
             for (int ks = 0; ks < BXS / 16; ++ks) xf[sl * (BXS / 16) + ks].v = rx.load(sb, ks, wave);
+            // 512-wide rows are 128 registers per lane, as many as the widest accumulator: together they fill the
+            // ordinary vector registers.  Left alone, the compiler parks the rows in accumulation registers and copies
+            // them back before the products of every column tile (122 copies per tile in the dQ kernel); defined in
+            // accumulation registers here, they are read from there by the matrix instructions themselves.
+            // (dK, whose column tiles carry E, fits the ordinary registers and gains nothing.)
+            if constexpr (D1 == 512 && OCC == 1 && !ELITE) {
+#pragma unroll
+                for (int ks = 0; ks < BXS / 16; ++ks) asm volatile("" : "+a"(xf[sl * (BXS / 16) + ks].v));
+            }
             if (MODE == MODE_H) {
                 if (a.variant == 0) {
                     // this slice's share of q~ . n_{k-1}: it fills matrix-unit time that the loads leave idle here
