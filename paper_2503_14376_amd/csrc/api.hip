@@ -230,7 +230,7 @@ int run_gates(const Dims& d, const float* i_pre, const float* f_pre, const float
 int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
              const float* n0, const float* m0, int B, int NH, int T, int Tvalid, int dqk_true, int dhv_true, int dqk, int dhv,
              int chunk, int variant, int dtype, float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
-             void* workspace, size_t workspace_bytes, void* stream) {
+             void* workspace, size_t workspace_bytes, void* stream, const LayerFuse* fz = nullptr) {
     const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype, true);
     if (rc != TFLA_OK) return rc;
     if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
@@ -269,6 +269,11 @@ int fwd_core(const void* q, const void* k, const void* v, const float* i_pre, co
     t.wrowB_out = is_exp ? w.wrowB : nullptr; t.sQ_out = is_exp ? w.sQ : nullptr;
     t.wrow_lo = w.wrow_lo; t.wcol_lo = w.ucol_lo; t.wrowB_lo_out = is_exp ? w.wrowB_lo : nullptr;
     t.dotwith = nullptr; t.dotpart = nullptr; t.E = nullptr;
+    if (fz) {
+        // the layer's output is formed by the H kernel itself (the caller has checked that its workgroups hold whole rows)
+        t.fz_o = fz->o_pre; t.fz_gamma = fz->gamma; t.fz_beta = fz->beta; t.fz_y = fz->y;
+        t.fz_kind = fz->kind; t.fz_NH = fz->NH; t.fz_eps = fz->eps;
+    }
     TFLA_LAUNCH(K_TILE_H, launch_tile_mode<MODE_H>(t, (int)d.BH, dtype, s));
 
     if (!is_exp) {
@@ -467,12 +472,13 @@ inline bool needs_pad(int T, int dqk, int dhv, int chunk) {
 int fwd_impl(const void* q, const void* k, const void* v, const float* i_pre, const float* f_pre, const float* C0,
              const float* n0, const float* m0, int B, int NH, int T, int dqk, int dhv, int chunk, int variant, int dtype,
              float eps, float softcap, void* H, float* Cn, float* nn, float* mn, float* n_out, float* m_out,
-             void* workspace, size_t workspace_bytes, void* stream) {
+             void* workspace, size_t workspace_bytes, void* stream, const LayerFuse* fz = nullptr) {
     const int rc = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype);
     if (rc != TFLA_OK) return rc;
     if (!needs_pad(T, dqk, dhv, chunk))
         return fwd_core(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, T, dqk, dhv, dqk, dhv, chunk, variant, dtype, eps, softcap, H,
-                        Cn, nn, mn, n_out, m_out, workspace, workspace_bytes, stream);
+                        Cn, nn, mn, n_out, m_out, workspace, workspace_bytes, stream, fz);
+    if (fz) return TFLA_ERR_SHAPE;      // (the fused layer output is for problems that need no padding)
     if (!q || !k || !v || !i_pre || !f_pre || !H) return TFLA_ERR_NULL;
     const bool is_exp = variant == TFLA_EXP;
     if (is_exp) {
@@ -826,9 +832,17 @@ int tfla_mlstm_layer_fwd(const void* q, const void* k, const void* v, const floa
     if (norm_kind != TFLA_NORM_RMS && norm_kind != TFLA_NORM_LAYER) return TFLA_ERR_ENUM;
     if (!(gate_softcap >= 0.0f) || !(norm_eps >= 0.0f)) return TFLA_ERR_SHAPE;
     if (!Y) return TFLA_ERR_NULL;
+    // Where a workgroup of the H kernel holds whole rows of h~ (bf16, d_hv of 64 or 128, nothing to pad), it forms
+    // y = sigma(o~) (.) NORM(h~) itself, next to h~: one read of h~ and one launch less.  Wider heads span several
+    // workgroups per row and take the separate kernel below.
+    const bool fuse = check_dims(TFLA_FWD, B, NH, T, dqk, dhv, chunk, variant, dtype) == TFLA_OK &&
+                      layer_fusion_applies(dqk, dhv, dtype, chunk) && !needs_pad(T, dqk, dhv, chunk) && !misaligned16(o_pre) &&
+                      !misaligned16(gamma) && !misaligned16(beta) && !misaligned16(Y);
+    const LayerFuse fz{o_pre, gamma, beta, Y, norm_kind, NH, norm_eps};
     const int rc = fwd_impl(q, k, v, i_pre, f_pre, C0, n0, m0, B, NH, T, dqk, dhv, chunk, variant, dtype, eps,
-                            gate_softcap, H, Cn, nn, mn, n_out, m_out, workspace, workspace_bytes, stream);
+                            gate_softcap, H, Cn, nn, mn, n_out, m_out, workspace, workspace_bytes, stream, fuse ? &fz : nullptr);
     if (rc != TFLA_OK) return rc;
+    if (fuse) return TFLA_OK;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     NormArgs a;
     a.h = H; a.o_pre = o_pre; a.gamma = gamma; a.beta = beta; a.y = Y;

@@ -205,6 +205,17 @@ struct TileArgs {
     // batch*head count, slices per XCD, and for each divisor its log2 when it is a power of two, else -1
     // (a division by a run-time value costs the start of every workgroup some forty instructions)
     int dec_bh, dec_bpx, sh_gx, sh_gy, sh_bpx, sh_nc;
+    // bf16 MODE_H, fused layer output (Sec. 2.1, hidden-state output equation: y = sigma(o~) (.) NORM(h~)), where one
+    // workgroup holds whole rows of h~ (d2 equal to the width of its column block, nothing padded): fz_y != NULL makes
+    // the kernel store y (BH, T, d2) next to h~.  fz_o: (BH, T, d2) gate pre-activations or NULL (gate = 1);
+    // fz_gamma / fz_beta: (fz_NH, d2) or NULL; fz_kind 0 = RMS norm, 1 = LayerNorm (as NormArgs).
+    const void* fz_o; const float* fz_gamma; const float* fz_beta; void* fz_y;
+    int fz_kind, fz_NH; float fz_eps;
+};
+// what the layer's forward entry point hands down to the H kernel when the fusion applies
+struct LayerFuse {
+    const void* o_pre; const float* gamma; const float* beta; void* y;
+    int kind, NH; float eps;
 };
 template <int MODE> hipError_t launch_tile_mode(const TileArgs& a, int BH, int dtype, hipStream_t s);
 // d2 block of a tiled kernel (mode MODE_*) with contraction width d1.  128 columns keep a bf16
@@ -225,6 +236,10 @@ inline int tile_bd2(int d1, int d2, int dtype, int mode, int L) {
     // (contractions over 1024 columns run as 512-wide halves with 128- or 64-wide blocks)
     if (d2 % 128 == 0) return 128;
     return 64;
+}
+// the fused layer output needs whole rows of h~ in one workgroup of the H kernel
+inline bool layer_fusion_applies(int dqk, int dhv, int dtype, int L) {
+    return dtype == 1 && (dhv == 64 || dhv == 128) && tile_bd2(dqk, dhv, dtype, MODE_H, L) == dhv;
 }
 
 }  // namespace tfla

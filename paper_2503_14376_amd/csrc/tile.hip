@@ -308,7 +308,17 @@ static hipError_t launch_tile_t(const TileArgs& a0, int BH, hipStream_t s) {
         constexpr int NOE = ((MODE == MODE_DQ || MODE == MODE_DK) && D1 <= TFLA_NOE_MAX_D1) ? 1 : 0;
         // a padded problem stores its true part straight into the caller's tensor (the first half of a split
         // contraction stores no output at all)
-        if (SPLIT != 1 && (a.out_T != a.T || a.out_ld != a.d2))
+        const bool padded = a.out_T != a.T || a.out_ld != a.d2;
+        if constexpr (MODE == MODE_H && SPLIT == 0 && BD2 <= 128) {
+            // the layer output next to h~: whole rows in one workgroup, nothing padded (the entry point has checked)
+            if (a.fz_y) {
+                if (padded || a.d2 != BD2) return hipErrorInvalidValue;
+                hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, 0, 0, 0, 1>), grid, dim3(64 * NW), 0, s, a);
+                return hipGetLastError();
+            }
+        }
+        if (a.fz_y) return hipErrorInvalidValue;
+        if (SPLIT != 1 && padded)
             hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT, NOE, SPLIT != 1>), grid, dim3(64 * NW), 0, s, a);
         else
             hipLaunchKernelGGL((tile_kernel_bf16<D1, BD2, NW, MODE, OCC, SPLIT, NOE, 0>), grid, dim3(64 * NW), 0, s, a);

@@ -49,8 +49,11 @@ __host__ __device__ constexpr int pre_item(int item, int BXS, int BCS) {
 // like every other mode (narrow contractions: E, L x L per chunk, is then more bytes than the operands it replaces).
 // PADOUT: 1 = the kernel runs on a zero-padded copy of the problem and stores only the true steps and columns,
 // straight into the caller's tensor (TileArgs::out_T, out_ld, out_cols); 0 = whole blocks, nothing padded.
-template <int D1, int BD2, int NW, int MODE, int OCC, int SPLIT = 0, int NOE = 0, int PADOUT = 0>
+// FUSE: 1 = MODE_H also stores the layer output y = sigma(o~) (.) NORM(h~) (Sec. 2.1, hidden-state output equation) of
+// its rows; the column block covers all of d2 (the launcher checks), nothing is padded.
+template <int D1, int BD2, int NW, int MODE, int OCC, int SPLIT = 0, int NOE = 0, int PADOUT = 0, int FUSE = 0>
 __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
+    static_assert(!FUSE || (MODE == MODE_H && SPLIT == 0 && !PADOUT), "the fused layer output belongs to the plain H kernel");
     using E = Elem<bf16_t>;
     using frag = E::frag;
     constexpr bool UPPER = (MODE & 1) != 0;
@@ -78,18 +81,18 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     static_assert(BD2 * BCS * 2 <= STAGE && BCS <= 64 && D1 % BCS == 0, "state slice must fit a stage");
 
     // after the loops the ring's memory holds the output block (and the dot operand) of each wave
-    constexpr int EPI = ((MODE == MODE_DQ || MODE == MODE_DK) ? 2 : 1) * NW * 32 * BD2 * 2;
+    constexpr bool WTILE = MODE == MODE_DQ || MODE == MODE_DK || FUSE;   // the epilogue reads a second per-wave tile
+    constexpr int EPI = (WTILE ? 2 : 1) * NW * 32 * BD2 * 2;
     constexpr int SMEM = NS * STAGE > EPI ? NS * STAGE : EPI;
     static_assert(SMEM <= BUDGET, "LDS budget");
     // The epilogue's per-wave tiles ([32][BD2] bf16: the output block on its way out and, for dQ / dK, the wave's rows
-    // of the dot operand) live in slots of the ring's memory.  Slots are numbered from the stage after the one that
+    // of the dot operand -- for the fused layer output, of the gate pre-activations) live in slots of the ring's memory.  Slots are numbered from the stage after the one that
     // holds the last ring item: the first (NS - 1) SPS of them are free while that item is being multiplied, so the dot
     // operand (slots 0 .. NW-1) is requested then and its latency hides behind the last tile; the output tiles take
     // the slots NW .. 2 NW - 1 once every wave has left the ring.
     constexpr int SLOT = 32 * BD2 * 2, SPS = STAGE / SLOT >= 1 ? STAGE / SLOT : 1;
     // (not where a slot is larger than a stage, and not in the first half of a split contraction, which has no epilogue)
-    constexpr bool WPRE = (MODE == MODE_DQ || MODE == MODE_DK) && SPLIT != 1 && STAGE >= SLOT && (NS - 1) * SPS >= NW &&
-                          NS * SPS >= 2 * NW;
+    constexpr bool WPRE = WTILE && SPLIT != 1 && STAGE >= SLOT && (NS - 1) * SPS >= NW && NS * SPS >= 2 * NW;
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     __shared__ __attribute__((aligned(1024))) char ldsE[EWRITE ? ESTG : 16];
     __shared__ __attribute__((aligned(256))) float ldsW[NS][NW][64];   // column weights of a tile, one copy per wave
@@ -396,9 +399,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
                 const int sl = wave, stg = (i + 1 + sl / SPS) % NS;
                 DmaTile<32, BD2, 64, SWZ_K> dw;
                 dw.init(d2, lane);
-                const bf16_t* wsrc = reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2;
+                const bf16_t* wsrc = reinterpret_cast<const bf16_t*>(FUSE ? a.fz_o : a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2;
                 const uint32_t wdst = smem_a + (uint32_t)(stg * STAGE + (sl % SPS) * SLOT);
-                if (gx == 1) dw.template issue<true>(wsrc, wdst, lane);
+                if (FUSE && !a.fz_o) {}                  // no output gate: nothing to fetch
+                else if (gx == 1) dw.template issue<true>(wsrc, wdst, lane);
                 else dw.issue(wsrc, wdst, lane);
             }
         }
@@ -588,13 +592,32 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
     auto slot_at = [&](int sl) { return smem + ((NI + sl / SPS) % NS) * STAGE + (sl % SPS) * SLOT; };
     char* otile = WPRE ? slot_at(NW + wave) : smem + wave * (32 * ORB);
     char* wtile = WPRE ? slot_at(wave) : smem + NW * (32 * ORB) + wave * (32 * ORB);
-    if ((MODE == MODE_DQ || MODE == MODE_DK) && !WPRE) {
-        DmaTile<32, BD2, 64, SWZ_K> dw;                  // this wave's rows of the dot operand
+    if (WTILE && !WPRE) {
+        DmaTile<32, BD2, 64, SWZ_K> dw;                  // this wave's rows of the dot operand (of the gate pre-activations)
         dw.init(d2, lane);
-        if (gx == 1)
-            dw.template issue<true>(reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2, lds_addr(wtile), lane);
-        else
-            dw.issue(reinterpret_cast<const bf16_t*>(a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2, lds_addr(wtile), lane);
+        const bf16_t* wsrc = reinterpret_cast<const bf16_t*>(FUSE ? a.fz_o : a.dotwith) + (tbase + wr0) * d2 + (long)nb2 * BD2;
+        if (FUSE && !a.fz_o) {}                          // no output gate: nothing to fetch
+        else if (gx == 1) dw.template issue<true>(wsrc, lds_addr(wtile), lane);
+        else dw.issue(wsrc, lds_addr(wtile), lane);
+    }
+    // fused layer output: this lane's eight columns of the per-head scale and shift (requested here, ahead of the
+    // output stores, so that the wait further down covers them together with the gate pre-activations)
+    float fz_g[8], fz_b[8];
+    if constexpr (FUSE) {
+        const int c8 = (lane % (BD2 / 8)) * 8;
+        const long hoff = (long)(bh % a.fz_NH) * d2 + c8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { fz_g[e] = 1.0f; fz_b[e] = 0.0f; }
+        if (a.fz_gamma) {
+            const f32x4 g0 = *reinterpret_cast<const f32x4*>(a.fz_gamma + hoff), g1 = *reinterpret_cast<const f32x4*>(a.fz_gamma + hoff + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { fz_g[e] = g0[e]; fz_g[4 + e] = g1[e]; }
+        }
+        if (a.fz_beta && a.fz_kind == 1) {
+            const f32x4 b0 = *reinterpret_cast<const f32x4*>(a.fz_beta + hoff), b1 = *reinterpret_cast<const f32x4*>(a.fz_beta + hoff + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { fz_b[e] = b0[e]; fz_b[4 + e] = b1[e]; }
+        }
     }
     const int fsw = swz_mask<SWZ_K, OCPR>(l32);
 #pragma unroll
@@ -629,6 +652,58 @@ __global__ void __launch_bounds__(NW * 64, OCC) tile_kernel_bf16(TileArgs a) {
                 if (ts0 + r < a.out_T && nb2 * BD2 + c * 8 < a.out_cols)
                     __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(obase + (long)r * a.out_ld * 2 + c * 16));
             }
+        }
+    }
+    if constexpr (FUSE) {
+        // y = sigma(o~) (.) (gamma (.) x^ + beta), x^ = (h~ - mean) rstd (LayerNorm) or h~ rstd (RMS norm), from the
+        // rounded h~ of the tile just stored: in the row-contiguous read-back a row's BD2 columns sit in BD2 / 8
+        // neighbouring lanes, eight columns each.  The gate pre-activations, the scale and the shift are older than
+        // the output stores above, so the wait leaves only those stores in flight.
+        constexpr int RPI = 64 / OCPR;
+        wait_vmcnt<32 / RPI>();
+        char* ybase = reinterpret_cast<char*>(a.fz_y) + ((tbase + wr0) * d2) * 2;
+        const float invd = 1.0f / (float)BD2;
+#pragma unroll
+        for (int q = 0; q < 32 / RPI; ++q) {
+            const int r = q * RPI + lane / OCPR, c = lane % OCPR;
+            const uint32_t toff = (uint32_t)(r * ORB + ((c ^ swz_mask<SWZ_K, OCPR>(r)) * 16));
+            const u32x4 hw = *reinterpret_cast<const u32x4*>(otile + toff);
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { x[2 * e] = bf16_lo_to_f32(hw[e]); x[2 * e + 1] = bf16_hi_to_f32(hw[e]); }
+            if (a.fz_kind == 1) {
+                float sm = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sm += x[e];
+#pragma unroll
+                for (int m = 1; m < OCPR; m <<= 1) sm += __shfl_xor(sm, m, 64);
+                const float mu = sm * invd;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] -= mu;
+            }
+            float ss = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+#pragma unroll
+            for (int m = 1; m < OCPR; m <<= 1) ss += __shfl_xor(ss, m, 64);
+            const float rstd = 1.0f / sqrtf(ss * invd + a.fz_eps);
+            float y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = x[e] * rstd * fz_g[e] + fz_b[e];
+            if (a.fz_o) {
+                const u32x4 ow = *reinterpret_cast<const u32x4*>(wtile + toff);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float o0 = bf16_lo_to_f32(ow[e]), o1 = bf16_hi_to_f32(ow[e]);
+                    const float e0 = expf(-fabsf(o0)), e1 = expf(-fabsf(o1));
+                    y[2 * e] *= o0 >= 0.0f ? 1.0f / (1.0f + e0) : e0 / (1.0f + e0);
+                    y[2 * e + 1] *= o1 >= 0.0f ? 1.0f / (1.0f + e1) : e1 / (1.0f + e1);
+                }
+            }
+            u32x4 yw;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) yw[e] = pack_bf16x2(y[2 * e], y[2 * e + 1]);
+            __builtin_nontemporal_store(yw, reinterpret_cast<u32x4*>(ybase + (long)r * d2 * 2 + c * 16));
         }
     }
     if (MODE == MODE_DQ || MODE == MODE_DK) {
