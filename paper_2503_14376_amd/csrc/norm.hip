@@ -214,6 +214,123 @@ __global__ void __launch_bounds__(256) norm_gate_bwd_kernel(NormBwdArgs a) {
     }
 }
 
+
+// ---- rows of 64, 128 or 256 values: LPR = d / 8 lanes per row, 64 / LPR rows of one wavefront side by side ----
+// (one row per wavefront would leave three quarters or more of the lanes idle)
+template <int LPR> __device__ __forceinline__ float row_sum(float x) {
+#pragma unroll
+    for (int m = 1; m < LPR; m <<= 1) x += __shfl_xor(x, m, 64);
+    return x;
+}
+// x (this lane's eight values of its row) -> x - mean for LayerNorm; returns 1 / sqrt(mean((x - mean)^2) + eps)
+template <int LPR> __device__ __forceinline__ float center_packed(float (&x)[8], int kind, float eps) {
+    constexpr float invd = 1.0f / (float)(LPR * 8);
+    if (kind == 1) {
+        float sm = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sm += x[e];
+        const float mu = row_sum<LPR>(sm) * invd;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] -= mu;
+    }
+    float ss = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+    return 1.0f / sqrtf(row_sum<LPR>(ss) * invd + eps);
+}
+
+template <typename DT, int LPR>
+__global__ void __launch_bounds__(256) norm_gate_fwd_packed_kernel(NormArgs a) {
+    constexpr int R = 64 / LPR, d = LPR * 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane / LPR, c = (lane % LPR) * 8;
+    const long row = ((long)blockIdx.x * 4 + wave) * R + sub;
+    const bool live = row < a.rows;
+    const long rr = live ? row : a.rows - 1;            // (lanes past the end repeat the last row and store nothing)
+    const int head = (int)((rr / a.T) % a.NH);
+    float x[8], g[8], be[8], o[8], y[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { g[e] = 1.0f; be[e] = 0.0f; o[e] = 0.0f; }
+    Row8<DT>::load(a.h, rr * d + c, x);
+    if (a.gamma) load8f(a.gamma + (long)head * d + c, g);
+    if (a.beta && a.kind == 1) load8f(a.beta + (long)head * d + c, be);
+    if (a.o_pre) Row8<DT>::load(a.o_pre, rr * d + c, o);
+    const float rstd = center_packed<LPR>(x, a.kind, a.eps);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float n = x[e] * rstd * g[e] + be[e];
+        y[e] = a.o_pre ? n * sigmoidf_(o[e]) : n;
+    }
+    if (live) Row8<DT>::store_stream(a.y, row * d + c, y);
+}
+
+template <typename DT, int LPR>
+__global__ void __launch_bounds__(256) norm_gate_bwd_packed_kernel(NormBwdArgs a) {
+    constexpr int R = 64 / LPR, d = LPR * 8;
+    __shared__ float red[4][2][d];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane / LPR, c = (lane % LPR) * 8;
+    const int bh = blockIdx.y, blk = blockIdx.x;
+    const int head = bh % a.NH;
+    float ag[8], ab[8], g[8], be[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ag[e] = 0.0f; ab[e] = 0.0f; g[e] = 1.0f; be[e] = 0.0f; }
+    if (a.gamma) load8f(a.gamma + (long)head * d + c, g);
+    if (a.beta && a.kind == 1) load8f(a.beta + (long)head * d + c, be);
+    const int t_end = min(a.T, (blk + 1) * NORM_RPB);
+    for (int t0 = blk * NORM_RPB + wave * R; t0 < t_end; t0 += 4 * R) {
+        const int t = t0 + sub;
+        const bool live = t < t_end;
+        const long row = (long)bh * a.T + (live ? t : t_end - 1);
+        float x[8], dy[8], o[8], dop[8], dx[8];
+        Row8<DT>::load(a.h, row * d + c, x);
+        Row8<DT>::load(a.dy, row * d + c, dy);
+        if (a.o_pre) Row8<DT>::load(a.o_pre, row * d + c, o);
+        const float rstd = center_packed<LPR>(x, a.kind, a.eps);
+        float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float xh = x[e] * rstd;
+            x[e] = xh;
+            float dn = dy[e];
+            if (a.o_pre) {
+                const float og = sigmoidf_(o[e]);
+                dop[e] = dy[e] * (xh * g[e] + be[e]) * og * (1.0f - og);
+                dn = dy[e] * og;
+            }
+            if (live) { ag[e] += dn * xh; ab[e] += dn; }
+            dx[e] = dn * g[e];
+            s1 += dx[e];
+            s2 += dx[e] * xh;
+        }
+        constexpr float invd = 1.0f / (float)d;
+        s1 = a.kind == 1 ? row_sum<LPR>(s1) * invd : 0.0f;
+        s2 = row_sum<LPR>(s2) * invd;
+        if (live) {
+            if (a.o_pre && a.do_pre) Row8<DT>::store_stream(a.do_pre, row * d + c, dop);
+            float dh[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dh[e] = rstd * (dx[e] - s1 - x[e] * s2);
+            Row8<DT>::store(a.dh, row * d + c, dh);
+        }
+    }
+    if (!a.part) return;
+    // the wavefront's R side-by-side rows add up first (lanes LPR apart hold the same columns), then the four wavefronts
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+#pragma unroll
+        for (int m = LPR; m < 64; m <<= 1) { ag[e] += __shfl_xor(ag[e], m, 64); ab[e] += __shfl_xor(ab[e], m, 64); }
+    }
+    if (sub == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { red[wave][0][c + e] = ag[e]; red[wave][1][c + e] = ab[e]; }
+    }
+    __syncthreads();
+    float* out = a.part + ((long)bh * gridDim.x + blk) * 2 * d;
+    for (int i = threadIdx.x; i < 2 * d; i += 256) {
+        const int w = i / d, cc = i - w * d;
+        out[i] = (red[0][w][cc] + red[1][w][cc]) + (red[2][w][cc] + red[3][w][cc]);
+    }
+}
+
 // d gamma[h][c] = sum over batch elements and row blocks of the partial sums (fixed order, fp64).
 // A workgroup takes 64 columns of one head; its four wavefronts split the (batch, row block) list.
 __global__ void __launch_bounds__(256) norm_param_grad_kernel(NormParamGradArgs a) {
@@ -274,7 +391,15 @@ __global__ void __launch_bounds__(256) transfer_gain_kernel(GainArgs a) {
     }
 }
 
+template <typename DT, int LPR> hipError_t norm_fwd_packed(const NormArgs& a, hipStream_t s) {
+    const long rpb = 4 * (64 / LPR);      // rows per workgroup
+    hipLaunchKernelGGL((norm_gate_fwd_packed_kernel<DT, LPR>), dim3((unsigned)((a.rows + rpb - 1) / rpb)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
 template <typename DT> hipError_t norm_fwd_dt(const NormArgs& a, hipStream_t s) {
+    if (a.d == 64) return norm_fwd_packed<DT, 8>(a, s);
+    if (a.d == 128) return norm_fwd_packed<DT, 16>(a, s);
+    if (a.d == 256) return norm_fwd_packed<DT, 32>(a, s);
     const dim3 grid((unsigned)((a.rows + 3) / 4));
     if (a.d <= 512) hipLaunchKernelGGL((norm_gate_fwd_kernel<DT, 1>), grid, dim3(256), 0, s, a);
     else if (a.d <= 1024) hipLaunchKernelGGL((norm_gate_fwd_kernel<DT, 2>), grid, dim3(256), 0, s, a);
@@ -283,6 +408,12 @@ template <typename DT> hipError_t norm_fwd_dt(const NormArgs& a, hipStream_t s) 
 }
 template <typename DT> hipError_t norm_bwd_dt(const NormBwdArgs& a, int BH, hipStream_t s) {
     const dim3 grid((a.T + NORM_RPB - 1) / NORM_RPB, BH);
+    if (a.d == 64 || a.d == 128 || a.d == 256) {
+        if (a.d == 64) hipLaunchKernelGGL((norm_gate_bwd_packed_kernel<DT, 8>), grid, dim3(256), 0, s, a);
+        else if (a.d == 128) hipLaunchKernelGGL((norm_gate_bwd_packed_kernel<DT, 16>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((norm_gate_bwd_packed_kernel<DT, 32>), grid, dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
     if (a.d <= 512) hipLaunchKernelGGL((norm_gate_bwd_kernel<DT, 1>), grid, dim3(256), 0, s, a);
     else if (a.d <= 1024) hipLaunchKernelGGL((norm_gate_bwd_kernel<DT, 2>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((norm_gate_bwd_kernel<DT, 4>), grid, dim3(256), 0, s, a);
