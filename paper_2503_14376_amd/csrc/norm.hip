@@ -332,15 +332,17 @@ __global__ void __launch_bounds__(256) norm_gate_bwd_packed_kernel(NormBwdArgs a
 }
 
 // d gamma[h][c] = sum over batch elements and row blocks of the partial sums (fixed order, fp64).
-// A workgroup takes 64 columns of one head; its four wavefronts split the (batch, row block) list.
-__global__ void __launch_bounds__(256) norm_param_grad_kernel(NormParamGradArgs a) {
-    __shared__ double red[4][2][64];
+// A workgroup takes 64 columns of one head; its sixteen wavefronts split the (batch, row block) list (the list is
+// a chain of dependent loads per wavefront, and there are only d / 64 x NH workgroups).
+constexpr int NPG_WAVES = 16;
+__global__ void __launch_bounds__(NPG_WAVES * 64) norm_param_grad_kernel(NormParamGradArgs a) {
+    __shared__ double red[NPG_WAVES][2][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = blockIdx.x * 64 + lane, head = blockIdx.y;
     double sg = 0.0, sb = 0.0;
     if (c < a.d) {
         const int n = a.B * a.nblk;
-        for (int i = wave; i < n; i += 4) {
+        for (int i = wave; i < n; i += NPG_WAVES) {
             const int b = i / a.nblk, blk = i - b * a.nblk;
             const float* p = a.part + (((long)b * a.NH + head) * a.nblk + blk) * 2 * a.d;
             sg += (double)p[c];
@@ -350,8 +352,9 @@ __global__ void __launch_bounds__(256) norm_param_grad_kernel(NormParamGradArgs 
     red[wave][0][lane] = sg; red[wave][1][lane] = sb;
     __syncthreads();
     if (wave == 0 && c < a.d) {
-        sg = (red[0][0][lane] + red[1][0][lane]) + (red[2][0][lane] + red[3][0][lane]);
-        sb = (red[0][1][lane] + red[1][1][lane]) + (red[2][1][lane] + red[3][1][lane]);
+        sg = 0.0; sb = 0.0;
+#pragma unroll
+        for (int w = 0; w < NPG_WAVES; ++w) { sg += red[w][0][lane]; sb += red[w][1][lane]; }
         if (a.dgamma) a.dgamma[(long)head * a.d + c] = (float)sg;
         if (a.dbeta) a.dbeta[(long)head * a.d + c] = (float)sb;
     }
@@ -437,7 +440,7 @@ hipError_t launch_norm_gate_bwd(const NormBwdArgs& a, int BH, hipStream_t s) {
     return a.dtype == 1 ? norm_bwd_dt<bf16_t>(a, BH, s) : norm_bwd_dt<float>(a, BH, s);
 }
 hipError_t launch_norm_param_grad(const NormParamGradArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL(norm_param_grad_kernel, dim3((a.d + 63) / 64, a.NH), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(norm_param_grad_kernel, dim3((a.d + 63) / 64, a.NH), dim3(NPG_WAVES * 64), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_transfer_gain(const GainArgs& a, int BH, hipStream_t s) {
